@@ -1,0 +1,236 @@
+#!/usr/bin/env python3
+"""Benchmark of the MoE-layer hot path on one MI355X.
+
+One step = one pass of the whole layer over one synthetic batch already resident in HBM:
+gating, micro-batch construction, the expert-block calls, the shared expert and the aggregation,
+all through the C ABI.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload prefill|decode|tenants]
+                    [--group-size g] [--policy p] [--shared-policy p] [--no-graph] [--no-cpu-baseline]
+
+The timed region runs the K steps twice: once eagerly with HIP events around each grouped-GEMM
+launch (these give the per-kernel durations the roofline figures use), and once as replays of a
+HIP graph of the same step (no host launch cost between kernels).  `value` comes from the graph
+replays unless --no-graph is given; both step times are in the JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import workloads  # noqa: E402
+
+PEAK_MFMA_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA peak
+PEAK_HBM_GBS = 8000.0            # MI355X HBM3E peak
+
+
+def layer_flops_per_token(s) -> int:
+    routed = 2 * 3 * s.H * s.I * s.K
+    shared = 2 * 3 * s.H * s.Is
+    router = 2 * s.H * s.E
+    gate = 2 * s.H if s.Is > 0 else 0
+    return routed + shared + router + gate
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="prefill", choices=["prefill", "decode", "tenants"])
+    ap.add_argument("--group-size", type=int, default=0, help="experts per expert block (0: one block)")
+    ap.add_argument("--policy", type=int, default=0)
+    ap.add_argument("--shared-policy", type=int, default=0)
+    ap.add_argument("--no-graph", action="store_true")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    args = ap.parse_args()
+
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU; the layer forward has no multi-GPU path "
+              "(token batches would shard without any exchange). Run with --gpus 1.", file=sys.stderr)
+        return 2
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback.", file=sys.stderr)
+        return 3
+
+    import paper_2604_26881_amd as moe
+    moe.load()
+
+    wl = {"prefill": workloads.prefill, "decode": workloads.decode, "tenants": workloads.tenants}[args.workload]()
+    s = wl.shape
+    g = wl.to("cuda")
+    shared = (g.Wsg, g.Wsu, g.Wsd, g.wgate) if s.Is > 0 else None
+    groups = workloads.partition(s.E, args.group_size) if args.group_size > 0 else [(0, s.E)]
+    buf = moe.LayerBuffers.allocate(s.T, s.H, s.E, s.K, s.I, s.Is)
+
+    def route():
+        if wl.tenant_rows is not None:
+            for i, (a, b) in enumerate(wl.tenant_rows):
+                moe.moe_route(g.x[a:b], g.Wr, g.bias[i], s.K, s.renorm, buf.topk_ids[a:b], buf.topk_w[a:b])
+        else:
+            moe.moe_route(g.x, g.Wr, g.bias, s.K, s.renorm, buf.topk_ids, buf.topk_w)
+
+    # phase bits of the *_ex policy word: 0x100 = gate/up kernel only, 0x200 = down kernel only
+    GU, DN = 0x100, 0x200
+    names = ["routed_gateup", "routed_down", "shared_gateup", "shared_down"]
+
+    def step(events=None):
+        route()
+        moe.moe_permute(buf.topk_ids, g.x, s.E, buf.expert_offsets, buf.src_of_row, buf.row_of_pair, buf.Xp)
+        if events is None:
+            for lo, hi in groups:
+                moe.moe_expert_group_forward(lo, hi, buf.Xp, buf.expert_offsets, g.Wg, g.Wu, g.Wd, buf.Yp,
+                                             buf.workspace, args.policy)
+            if shared is not None:
+                moe.moe_shared_forward(g.x, *shared, buf.S, buf.sg, buf.workspace_shared, args.shared_policy)
+        else:
+            # same kernels, launched one per call so that events can bracket each of them
+            ev = [[torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)] for _ in names]
+            ev[0][0].record()
+            for lo, hi in groups:
+                moe.moe_expert_group_forward(lo, hi, buf.Xp, buf.expert_offsets, g.Wg, g.Wu, g.Wd, buf.Yp,
+                                             buf.workspace, args.policy | GU)
+            ev[0][1].record()
+            ev[1][0].record()
+            for lo, hi in groups:
+                moe.moe_expert_group_forward(lo, hi, buf.Xp, buf.expert_offsets, g.Wg, g.Wu, g.Wd, buf.Yp,
+                                             buf.workspace, args.policy | DN)
+            ev[1][1].record()
+            if shared is not None:
+                ev[2][0].record()
+                moe.moe_shared_forward(g.x, *shared, buf.S, buf.sg, buf.workspace_shared, args.shared_policy | GU)
+                ev[2][1].record()
+                ev[3][0].record()
+                moe.moe_shared_forward(g.x, *shared, buf.S, buf.sg, buf.workspace_shared, args.shared_policy | DN)
+                ev[3][1].record()
+            events.append(ev)
+        moe.moe_combine(buf.Yp, buf.row_of_pair, buf.topk_w, buf.S, buf.sg, buf.out)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    # ---- timed region 1: eager, events around the four grouped-GEMM launches
+    events = []
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(events)
+    torch.cuda.synchronize()
+    eager_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    kern_ms = {}
+    for i, n in enumerate(names):
+        if shared is None and i >= 2:
+            continue
+        kern_ms[n] = float(np.mean([ev[i][0].elapsed_time(ev[i][1]) for ev in events]))
+
+    # ---- timed region 2: the same step as HIP-graph replays
+    graph_ms = None
+    if not args.no_graph:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            for _ in range(3):
+                step()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        for _ in range(max(3, args.warmup)):
+            graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    ms = graph_ms if graph_ms is not None else eager_ms
+    tokens_per_s = s.T / (ms * 1e-3)
+    flop_tok = layer_flops_per_token(s)
+    layer_tflops = flop_tok * s.T / (ms * 1e-3) / 1e12
+
+    # ---- roofline of the dominant grouped-GEMM kernel
+    counts = torch.diff(buf.expert_offsets).cpu().numpy()
+    active = int((counts > 0).sum())
+    P = s.P
+    alg_flops = {"routed_gateup": 2 * 2 * P * s.H * s.I, "routed_down": 2 * P * s.H * s.I,
+                 "shared_gateup": 2 * 2 * s.T * s.H * s.Is, "shared_down": 2 * s.T * s.H * s.Is}
+    alg_bytes = {"routed_gateup": active * 2 * s.I * s.H * 2 + P * s.H * 2 + P * s.I * 2,
+                 "routed_down": active * s.I * s.H * 2 + P * s.I * 2 + P * s.H * 2,
+                 "shared_gateup": 2 * s.Is * s.H * 2 + s.T * s.H * 2 + s.T * s.Is * 2,
+                 "shared_down": s.Is * s.H * 2 + s.T * s.Is * 2 + s.T * s.H * 2}
+    dom = max(kern_ms, key=kern_ms.get)
+    launches = len(groups) if dom.startswith("routed") else 1
+    dur_s = kern_ms[dom] * 1e-3 / launches      # average duration of one launch
+    ridge = PEAK_MFMA_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9)
+    intensity = alg_flops[dom] / alg_bytes[dom]
+    if intensity >= ridge:
+        achieved = alg_flops[dom] / launches / dur_s / 1e12
+        roof = {"bound": "mfma", "achieved": achieved, "peak": PEAK_MFMA_BF16_TFLOPS, "unit": "TFLOP/s",
+                "frac": achieved / PEAK_MFMA_BF16_TFLOPS, "traffic": None}
+    else:
+        achieved = alg_bytes[dom] / launches / dur_s / 1e9
+        roof = {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                "frac": achieved / PEAK_HBM_GBS, "traffic": None}
+    roof.update({"kernel": dom, "launch_us": dur_s * 1e6, "launches_per_step": launches,
+                 "algorithmic_flops_per_launch": alg_flops[dom] / launches,
+                 "algorithmic_bytes_per_launch": alg_bytes[dom] / launches})
+    kernels = {n: {"ms_per_step": kern_ms[n], "tflops": alg_flops[n] / (kern_ms[n] * 1e-3) / 1e12,
+                   "gbs": alg_bytes[n] / (kern_ms[n] * 1e-3) / 1e9} for n in kern_ms}
+
+    # whole-layer fractions against both roofs (weights of active experts + shared + activations)
+    layer_bytes = sum(alg_bytes[n] for n in kern_ms) + s.E * s.H * 2 + 2 * s.T * s.H * 2 + 2 * P * s.H * 2
+    out = {
+        "metric": "moe_layer_tokens_per_s", "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: Qwen1.5-MoE-2.7B-shaped layer, T={s.T}", "T": s.T, "H": s.H,
+                   "E": s.E, "K": s.K, "I": s.I, "Is": s.Is, "renorm": s.renorm, "expert_blocks": len(groups),
+                   "policy": args.policy, "shared_policy": args.shared_policy,
+                   "launch": "hip graph replay" if graph_ms is not None else "eager",
+                   "active_experts": active, "rows_per_expert_max": int(counts.max()),
+                   "rows_per_expert_median": float(np.median(counts))},
+        "ms_per_step_eager": eager_ms, "ms_per_step_graph": graph_ms,
+        "layer_tflops": layer_tflops, "layer_frac_of_mfma_peak": layer_tflops / PEAK_MFMA_BF16_TFLOPS,
+        "layer_gbs": layer_bytes / (ms * 1e-3) / 1e9, "layer_frac_of_hbm_peak": layer_bytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+        "flop_per_token": flop_tok, "roofline": roof, "kernels": kernels,
+    }
+
+    # ---- CPU baseline: the oracle, per-token definition, on a bounded sample of the same batch
+    if not args.no_cpu_baseline:
+        import oracle
+        orc = oracle.Oracle("f64")
+        d = wl.f32_numpy()
+        cores = orc.num_threads()
+        sh = None if s.Is == 0 else (d["Wsg"], d["Wsu"], d["Wsd"], d["wgate"])
+        done, t_cpu, batch = 0, 0.0, max(cores * 4, 16)
+        while t_cpu < args.cpu_seconds and done < s.T:
+            tok = np.arange(done, min(s.T, done + batch), dtype=np.int32)
+            bias = d["bias"]
+            if wl.tenant_rows is not None:
+                bias = bias[0]
+            t0 = time.perf_counter()
+            orc.token_forward(tok, d["x"], d["Wr"], bias, d["Wg"], d["Wu"], d["Wd"], sh, s.K, s.renorm)
+            t_cpu += time.perf_counter() - t0
+            done += len(tok)
+        out["cpu_baseline"] = {"value": done / t_cpu, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+                               "sample": f"first {done} tokens of the same batch, float64 per-token definition, "
+                                         f"{t_cpu:.1f} s"}
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

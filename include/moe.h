@@ -1,0 +1,161 @@
+/*
+ * moe.h - C ABI of the MI355X (gfx950) MoE-layer forward library.
+ *
+ * The calls follow the split the FaaSMoE paper makes (Sec. 3 "Architecture"): a control plane
+ * (the orchestrator: gating, construction of one micro-batch per expert block, aggregation) and
+ * an execution plane (expert blocks: stateless functions that hold a configurable number of
+ * experts and compute on the tokens they are handed).  moe_route, moe_permute and moe_combine
+ * are the control plane; moe_expert_group_forward is one expert-block invocation;
+ * moe_shared_forward runs the model's shared experts (Sec. 5 "Model Selection": 60 routed and
+ * 4 shared experts per layer), which no routed-expert block contains.
+ *
+ * Conventions for every call
+ *  - Every pointer is a DEVICE pointer owned by the caller.  The library allocates nothing,
+ *    frees nothing and keeps no pointer after the call returns.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only enqueue
+ *    kernels on it; they never synchronise and never read device memory on the host.
+ *  - Activations and weights are bf16 (16-bit, upper half of an IEEE fp32), row-major, innermost
+ *    dimension contiguous; accumulation is fp32.  Indices are int32.
+ *  - Return value: MOE_OK (0), or a negative MOE_ERR_* code, in which case nothing was enqueued.
+ *  - No hidden state: the result of a call is a function of its arguments alone (Sec. 3: expert
+ *    blocks are stateless; the orchestrator keeps no cross-request state), so a call may be
+ *    repeated, and calls on disjoint outputs may be issued in any order or on several streams.
+ *  - Shape limits: H, I, Is multiples of 64; 1 <= K <= 16; K <= E <= 256; T*K < 2^31 / max(H,I).
+ *
+ * Symbols: T tokens, H hidden size, E routed experts, K experts per token, P = T*K
+ * (token, slot) pairs, I routed-expert intermediate size, Is shared-expert intermediate size.
+ */
+#ifndef MOE_H_
+#define MOE_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MOE_OK 0
+#define MOE_ERR_NULL (-1)      /* a required pointer is NULL */
+#define MOE_ERR_SHAPE (-2)     /* a size or an expert range is outside the limits above */
+#define MOE_ERR_WORKSPACE (-3) /* workspace_bytes is smaller than the call needs */
+#define MOE_ERR_LAUNCH (-4)    /* the HIP runtime refused a kernel launch */
+
+/* Human-readable text for a status code (static storage, never NULL). */
+const char* moe_status_string(int status);
+
+/*
+ * Gating (Sec. 2.1: the gating network selects the top-k experts per token; Sec. 3: it runs in
+ * the orchestrator).
+ *   logit[t,e] = <x[t,:], Wr[e,:]> + bias[e]      fp32, in a fixed summation order (below)
+ *   p[t,:]     = softmax over e of logit[t,:]      fp32
+ *   topk_ids[t,0..K-1] = the K experts with the largest logits, descending; equal logits (and
+ *                        -0 / +0) go to the lower expert id
+ *   topk_w[t,j] = p[t, topk_ids[t,j]], divided by their sum over j when renorm != 0
+ * Summation order of the dot product: element h belongs to partial sum (h/8) mod 64; each
+ * partial takes its elements in ascending h by fused multiply-add starting from +0; the 64
+ * partials are folded by a butterfly a[j] += a[j xor s] for s = 32,16,8,4,2,1; the bias is added
+ * last.  bf16 products are exact in fp32, so the logits are reproducible bit for bit.
+ * Row t of the outputs depends on row t of x only, so slices of a batch (one per tenant, each
+ * with its own bias) may be routed by separate calls.
+ *   x [T,H] bf16; Wr [E,H] bf16; bias [E] fp32 or NULL; topk_ids [T,K] int32; topk_w [T,K] fp32.
+ * T == 0 is a no-op.
+ */
+int moe_route(const void* x, const void* Wr, const float* bias, int T, int H, int E, int K,
+              int renorm, int32_t* topk_ids, float* topk_w, void* stream);
+
+/*
+ * Micro-batch construction (Sec. 3: after gating the orchestrator builds micro-batched routing
+ * requests; Sec. 4.1: all tokens routed to one expert block are consolidated into one batched
+ * invocation).  A stable counting sort of the P pairs p = t*K + j by expert id:
+ *   expert_offsets[e] .. expert_offsets[e+1]-1 are the rows of expert e (expert_offsets[E] = P);
+ *   row_of_pair[p] = row that pair p lands on; src_of_row[r] = the pair on row r (its inverse);
+ *   inside one expert the rows keep ascending p;  Xp[r,:] = x[src_of_row[r] / K, :].
+ * The batch of an expert block [lo,hi) is therefore the contiguous row range
+ * expert_offsets[lo] .. expert_offsets[hi]-1 of Xp.
+ *   topk_ids [T,K] int32 with values in [0,E) (values outside are not detected);
+ *   x [T,H] bf16; expert_offsets [E+1]; src_of_row [P]; row_of_pair [P]; Xp [P,H] bf16.
+ * workspace: not used at present (may be NULL); moe_permute_workspace_bytes returns 0.
+ */
+int moe_permute(const int32_t* topk_ids, const void* x, int T, int H, int E, int K,
+                int32_t* expert_offsets, int32_t* src_of_row, int32_t* row_of_pair, void* Xp,
+                void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * One expert-block invocation (Sec. 3: an expert block packages a configurable number of
+ * experts behind one function and computes statelessly on the tokens assigned to it).
+ * For every expert e in [group_lo, group_hi) and every row r of that expert:
+ *   h[r,:]  = silu(Xp[r,:] . Wg[e]^T) * (Xp[r,:] . Wu[e]^T)        silu(a) = a / (1 + exp(-a))
+ *   Yp[r,:] = h[r,:] . Wd[e]^T
+ * The gate weight is NOT applied here (the block sees tokens only); moe_combine applies it.
+ * Only rows expert_offsets[group_lo] .. expert_offsets[group_hi]-1 of Yp are written; experts
+ * without rows cost nothing and their weights are not read.  The result for a row does not
+ * depend on how [0,E) is cut into blocks (Sec. 3: block size does not change model semantics).
+ *   Xp [P,H] bf16; expert_offsets [E+1] int32 ON THE DEVICE (read by the kernels);
+ *   Wg, Wu [E,I,H] bf16; Wd [E,H,I] bf16 (the full tensors, not the block's slice);
+ *   Yp [P,H] bf16.
+ * workspace: moe_expert_workspace_bytes(P, I) bytes, holding h (bf16 [P,I]).  Blocks that run
+ * concurrently may share one workspace: each touches only its own rows.
+ */
+int moe_expert_group_forward(int group_lo, int group_hi, const void* Xp,
+                             const int32_t* expert_offsets, const void* Wg, const void* Wu,
+                             const void* Wd, int P, int H, int E, int I, void* Yp,
+                             void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Shared experts (Sec. 5: 4 shared experts per layer, here as one SwiGLU FFN whose
+ * intermediate size Is is the four concatenated) on every token, and the raw logit of their
+ * sigmoid gate:
+ *   S[t,:] = ( silu(x[t,:] . Wsg^T) * (x[t,:] . Wsu^T) ) . Wsd^T ;   sg[t] = <x[t,:], wgate>
+ *   x [T,H]; Wsg, Wsu [Is,H]; Wsd [H,Is]; wgate [H] (bf16) or NULL (then sg is not written);
+ *   S [T,H] bf16; sg [T] fp32.
+ * workspace: moe_shared_workspace_bytes(T, Is) bytes.
+ */
+int moe_shared_forward(const void* x, const void* Wsg, const void* Wsu, const void* Wsd,
+                       const void* wgate, int T, int H, int Is, void* S, float* sg,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Aggregation (Sec. 3 and Sec. 4.2: the orchestrator aggregates the tokens that come back from
+ * the expert blocks):
+ *   out[t,:] = sum over j = 0..K-1, in that order, of topk_w[t,j] * Yp[row_of_pair[t*K+j],:]
+ *              + sigmoid(sg[t]) * S[t,:]                       (fp32, rounded once to bf16)
+ * S and sg may both be NULL (no shared expert).  The sum order is fixed, so `out` is bitwise
+ * independent of how the experts were cut into blocks and of the order the blocks ran in.
+ *   Yp [T*K,H] bf16; row_of_pair [T*K]; topk_w [T,K] fp32; S [T,H] bf16; sg [T] fp32;
+ *   out [T,H] bf16.
+ */
+int moe_combine(const void* Yp, const int32_t* row_of_pair, const float* topk_w, const void* S,
+                const float* sg, int T, int H, int K, void* out, void* stream);
+
+/*
+ * The same two calls with the kernel shape picked by the caller instead of by the library
+ * (measurement and tuning).  policy: 0 = automatic (what the plain calls use); 1 = weight-streaming
+ * kernels, one 16-row weight block per wave; 2 = weight-streaming kernels with K split over the 4
+ * waves of a workgroup; 3 = MFMA tiles of 128 token rows; 4 = MFMA tiles of 256 token rows.
+ * Every policy computes the same function; results may differ in the last bf16 bit between
+ * policies because the fp32 summation order differs.  Use one policy for all blocks of a layer.
+ * Adding 0x100 to policy runs only the first kernel of the call (gate/up projections and SwiGLU
+ * into the workspace), adding 0x200 only the second (down projection from the workspace, and for
+ * the shared expert the gate logit): the two halves of one call, so each can be timed alone.
+ */
+int moe_expert_group_forward_ex(int group_lo, int group_hi, const void* Xp,
+                                const int32_t* expert_offsets, const void* Wg, const void* Wu,
+                                const void* Wd, int P, int H, int E, int I, void* Yp,
+                                void* workspace, size_t workspace_bytes, int policy, void* stream);
+int moe_shared_forward_ex(const void* x, const void* Wsg, const void* Wsu, const void* Wsd,
+                          const void* wgate, int T, int H, int Is, void* S, float* sg,
+                          void* workspace, size_t workspace_bytes, int policy, void* stream);
+
+/* Workspace sizes in bytes (multiples of 256). */
+size_t moe_permute_workspace_bytes(int T, int K, int E);
+size_t moe_expert_workspace_bytes(int P, int I);
+size_t moe_shared_workspace_bytes(int T, int Is);
+/* Largest of the three: one buffer of this size serves every call of a layer issued on one
+ * stream. */
+size_t moe_workspace_bytes(int T, int H, int E, int K, int I, int Is);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOE_H_ */

@@ -1,0 +1,12 @@
+"""MI355X (gfx950) MoE-layer forward: routed experts invoked as stateless expert blocks.
+
+The compute lives in ``libmoe_hip.so`` (hand-written HIP kernels behind the C ABI declared in
+``include/moe.h``).  This package is only the ctypes binding: it marshals torch tensors (device
+memory and the current stream) into those calls.  There is no CPU or PyTorch fallback: if the
+library is missing or no GPU is present, the calls raise.
+"""
+from .binding import (MoeError, lib_path, load, moe_combine, moe_expert_group_forward, moe_layer_forward,
+                      moe_permute, moe_route, moe_shared_forward, moe_workspace_bytes, LayerBuffers)
+
+__all__ = ["MoeError", "lib_path", "load", "moe_route", "moe_permute", "moe_expert_group_forward",
+           "moe_shared_forward", "moe_combine", "moe_workspace_bytes", "moe_layer_forward", "LayerBuffers"]

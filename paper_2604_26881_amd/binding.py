@@ -1,0 +1,233 @@
+"""ctypes binding of libmoe_hip.so: same names and argument order as include/moe.h.
+
+Argument marshalling only.  Tensors must live on the GPU, be contiguous and have the dtype the
+C interface states; outputs are allocated with torch when not passed in.  Work is enqueued on
+torch's current stream.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import List, Optional, Sequence, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB = None
+
+SYMBOLS = ["moe_status_string", "moe_route", "moe_permute", "moe_expert_group_forward",
+           "moe_expert_group_forward_ex", "moe_shared_forward", "moe_shared_forward_ex", "moe_combine",
+           "moe_permute_workspace_bytes", "moe_expert_workspace_bytes", "moe_shared_workspace_bytes",
+           "moe_workspace_bytes"]
+
+
+class MoeError(RuntimeError):
+    pass
+
+
+def lib_path() -> str:
+    return os.path.join(_HERE, "libmoe_hip.so")
+
+
+def load() -> ctypes.CDLL:
+    """Load the built library (building it first only if it does not exist)."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    if not os.path.exists(lib_path()):
+        from . import build as _build
+        _build.build()
+    lib = ctypes.CDLL(lib_path())
+    c_int, c_vp, c_sz = ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t
+    lib.moe_status_string.restype = ctypes.c_char_p
+    lib.moe_status_string.argtypes = [c_int]
+    lib.moe_route.restype = c_int
+    lib.moe_route.argtypes = [c_vp, c_vp, c_vp, c_int, c_int, c_int, c_int, c_int, c_vp, c_vp, c_vp]
+    lib.moe_permute.restype = c_int
+    lib.moe_permute.argtypes = [c_vp, c_vp, c_int, c_int, c_int, c_int, c_vp, c_vp, c_vp, c_vp, c_vp, c_sz, c_vp]
+    lib.moe_expert_group_forward.restype = c_int
+    lib.moe_expert_group_forward.argtypes = [c_int, c_int, c_vp, c_vp, c_vp, c_vp, c_vp, c_int, c_int, c_int, c_int,
+                                             c_vp, c_vp, c_sz, c_vp]
+    lib.moe_expert_group_forward_ex.restype = c_int
+    lib.moe_expert_group_forward_ex.argtypes = [c_int, c_int, c_vp, c_vp, c_vp, c_vp, c_vp, c_int, c_int, c_int,
+                                                c_int, c_vp, c_vp, c_sz, c_int, c_vp]
+    lib.moe_shared_forward.restype = c_int
+    lib.moe_shared_forward.argtypes = [c_vp, c_vp, c_vp, c_vp, c_vp, c_int, c_int, c_int, c_vp, c_vp, c_vp, c_sz, c_vp]
+    lib.moe_shared_forward_ex.restype = c_int
+    lib.moe_shared_forward_ex.argtypes = [c_vp, c_vp, c_vp, c_vp, c_vp, c_int, c_int, c_int, c_vp, c_vp, c_vp, c_sz,
+                                          c_int, c_vp]
+    lib.moe_combine.restype = c_int
+    lib.moe_combine.argtypes = [c_vp, c_vp, c_vp, c_vp, c_vp, c_int, c_int, c_int, c_vp, c_vp]
+    for n in ("moe_permute_workspace_bytes", "moe_expert_workspace_bytes", "moe_shared_workspace_bytes"):
+        getattr(lib, n).restype = c_sz
+    lib.moe_permute_workspace_bytes.argtypes = [c_int, c_int, c_int]
+    lib.moe_expert_workspace_bytes.argtypes = [c_int, c_int]
+    lib.moe_shared_workspace_bytes.argtypes = [c_int, c_int]
+    lib.moe_workspace_bytes.restype = c_sz
+    lib.moe_workspace_bytes.argtypes = [c_int] * 6
+    _LIB = lib
+    return lib
+
+
+def _check(rc: int, what: str) -> None:
+    if rc != 0:
+        raise MoeError(f"{what}: {load().moe_status_string(rc).decode()} (status {rc})")
+
+
+def _ptr(t: Optional[torch.Tensor], dtype: Optional[torch.dtype], name: str) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise MoeError(f"{name} must be a GPU tensor")
+    if not t.is_contiguous():
+        raise MoeError(f"{name} must be contiguous")
+    if dtype is not None and t.dtype != dtype:
+        raise MoeError(f"{name} must be {dtype}, got {t.dtype}")
+    return t.data_ptr()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def moe_workspace_bytes(T: int, H: int, E: int, K: int, I: int, Is: int) -> int:
+    return int(load().moe_workspace_bytes(T, H, E, K, I, Is))
+
+
+def moe_route(x, Wr, bias, K: int, renorm: bool, topk_ids=None, topk_w=None):
+    T, H = x.shape
+    E = Wr.shape[0]
+    if topk_ids is None:
+        topk_ids = torch.empty((T, K), dtype=torch.int32, device=x.device)
+    if topk_w is None:
+        topk_w = torch.empty((T, K), dtype=torch.float32, device=x.device)
+    rc = load().moe_route(_ptr(x, torch.bfloat16, "x"), _ptr(Wr, torch.bfloat16, "Wr"),
+                          _ptr(bias, torch.float32, "bias"), T, H, E, K, int(bool(renorm)),
+                          _ptr(topk_ids, torch.int32, "topk_ids"), _ptr(topk_w, torch.float32, "topk_w"), _stream())
+    _check(rc, "moe_route")
+    return topk_ids, topk_w
+
+
+def moe_permute(topk_ids, x, E: int, expert_offsets=None, src_of_row=None, row_of_pair=None, Xp=None):
+    T, K = topk_ids.shape
+    H = x.shape[1]
+    dev = x.device
+    if expert_offsets is None:
+        expert_offsets = torch.empty(E + 1, dtype=torch.int32, device=dev)
+    if src_of_row is None:
+        src_of_row = torch.empty(T * K, dtype=torch.int32, device=dev)
+    if row_of_pair is None:
+        row_of_pair = torch.empty(T * K, dtype=torch.int32, device=dev)
+    if Xp is None:
+        Xp = torch.empty((T * K, H), dtype=torch.bfloat16, device=dev)
+    rc = load().moe_permute(_ptr(topk_ids, torch.int32, "topk_ids"), _ptr(x, torch.bfloat16, "x"), T, H, E, K,
+                            _ptr(expert_offsets, torch.int32, "expert_offsets"),
+                            _ptr(src_of_row, torch.int32, "src_of_row"),
+                            _ptr(row_of_pair, torch.int32, "row_of_pair"), _ptr(Xp, torch.bfloat16, "Xp"), None, 0,
+                            _stream())
+    _check(rc, "moe_permute")
+    return expert_offsets, src_of_row, row_of_pair, Xp
+
+
+def moe_expert_group_forward(group_lo: int, group_hi: int, Xp, expert_offsets, Wg, Wu, Wd, Yp, workspace,
+                             policy: int = 0):
+    P, H = Xp.shape
+    E, I, _ = Wg.shape
+    rc = load().moe_expert_group_forward_ex(int(group_lo), int(group_hi), _ptr(Xp, torch.bfloat16, "Xp"),
+                                            _ptr(expert_offsets, torch.int32, "expert_offsets"),
+                                            _ptr(Wg, torch.bfloat16, "Wg"), _ptr(Wu, torch.bfloat16, "Wu"),
+                                            _ptr(Wd, torch.bfloat16, "Wd"), P, H, E, I,
+                                            _ptr(Yp, torch.bfloat16, "Yp"), _ptr(workspace, None, "workspace"),
+                                            0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                            int(policy), _stream())
+    _check(rc, "moe_expert_group_forward")
+    return Yp
+
+
+def moe_shared_forward(x, Wsg, Wsu, Wsd, wgate, S, sg, workspace, policy: int = 0):
+    T, H = x.shape
+    Is = Wsg.shape[0]
+    rc = load().moe_shared_forward_ex(_ptr(x, torch.bfloat16, "x"), _ptr(Wsg, torch.bfloat16, "Wsg"),
+                                      _ptr(Wsu, torch.bfloat16, "Wsu"), _ptr(Wsd, torch.bfloat16, "Wsd"),
+                                      _ptr(wgate, torch.bfloat16, "wgate"), T, H, Is, _ptr(S, torch.bfloat16, "S"),
+                                      _ptr(sg, torch.float32, "sg"), _ptr(workspace, None, "workspace"),
+                                      0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                      int(policy), _stream())
+    _check(rc, "moe_shared_forward")
+    return S, sg
+
+
+def moe_combine(Yp, row_of_pair, topk_w, S, sg, out=None):
+    T, K = topk_w.shape
+    H = Yp.shape[1]
+    if out is None:
+        out = torch.empty((T, H), dtype=torch.bfloat16, device=Yp.device)
+    rc = load().moe_combine(_ptr(Yp, torch.bfloat16, "Yp"), _ptr(row_of_pair, torch.int32, "row_of_pair"),
+                            _ptr(topk_w, torch.float32, "topk_w"), _ptr(S, torch.bfloat16, "S"),
+                            _ptr(sg, torch.float32, "sg"), T, H, K, _ptr(out, torch.bfloat16, "out"), _stream())
+    _check(rc, "moe_combine")
+    return out
+
+
+@dataclass
+class LayerBuffers:
+    """Every output and scratch tensor of one layer forward, allocated once and reused."""
+    topk_ids: torch.Tensor
+    topk_w: torch.Tensor
+    expert_offsets: torch.Tensor
+    src_of_row: torch.Tensor
+    row_of_pair: torch.Tensor
+    Xp: torch.Tensor
+    Yp: torch.Tensor
+    S: Optional[torch.Tensor]
+    sg: Optional[torch.Tensor]
+    out: torch.Tensor
+    workspace: torch.Tensor
+    workspace_shared: Optional[torch.Tensor]
+
+    @staticmethod
+    def allocate(T: int, H: int, E: int, K: int, I: int, Is: int, device="cuda") -> "LayerBuffers":
+        lib = load()
+        P = T * K
+        i32 = dict(dtype=torch.int32, device=device)
+        bf = dict(dtype=torch.bfloat16, device=device)
+        ws = max(int(lib.moe_expert_workspace_bytes(P, I)), 256)
+        wss = int(lib.moe_shared_workspace_bytes(T, Is))
+        return LayerBuffers(
+            topk_ids=torch.empty((T, K), **i32), topk_w=torch.empty((T, K), dtype=torch.float32, device=device),
+            expert_offsets=torch.empty(E + 1, **i32), src_of_row=torch.empty(P, **i32),
+            row_of_pair=torch.empty(P, **i32), Xp=torch.empty((P, H), **bf), Yp=torch.empty((P, H), **bf),
+            S=torch.empty((T, H), **bf) if Is > 0 else None,
+            sg=torch.empty(T, dtype=torch.float32, device=device) if Is > 0 else None,
+            out=torch.empty((T, H), **bf), workspace=torch.empty(ws, dtype=torch.uint8, device=device),
+            workspace_shared=torch.empty(max(wss, 256), dtype=torch.uint8, device=device) if Is > 0 else None)
+
+
+def moe_layer_forward(x, Wr, bias, Wg, Wu, Wd, shared, K: int, renorm: bool,
+                      groups: Optional[Sequence[Tuple[int, int]]] = None, buf: Optional[LayerBuffers] = None,
+                      tenant_rows: Optional[List[Tuple[int, int]]] = None, policy: int = 0,
+                      shared_policy: int = 0) -> LayerBuffers:
+    """One MoE layer in the paper's order: gating, micro-batch construction, one call per expert
+    block, shared expert, aggregation.  Sequencing only; every step is a library call.
+
+    shared: (Wsg, Wsu, Wsd, wgate) or None.  groups: expert blocks (lo, hi), default one block.
+    tenant_rows with a [n_tenants, E] bias: gating is called once per tenant slice."""
+    T, H = x.shape
+    E, I, _ = Wg.shape
+    Is = 0 if shared is None else shared[0].shape[0]
+    if buf is None:
+        buf = LayerBuffers.allocate(T, H, E, K, I, Is, x.device)
+    if tenant_rows is not None:
+        for i, (a, b) in enumerate(tenant_rows):
+            moe_route(x[a:b], Wr, None if bias is None else bias[i], K, renorm, buf.topk_ids[a:b], buf.topk_w[a:b])
+    else:
+        moe_route(x, Wr, bias, K, renorm, buf.topk_ids, buf.topk_w)
+    moe_permute(buf.topk_ids, x, E, buf.expert_offsets, buf.src_of_row, buf.row_of_pair, buf.Xp)
+    for lo, hi in (groups or [(0, E)]):
+        moe_expert_group_forward(lo, hi, buf.Xp, buf.expert_offsets, Wg, Wu, Wd, buf.Yp, buf.workspace, policy)
+    if shared is not None:
+        moe_shared_forward(x, shared[0], shared[1], shared[2], shared[3], buf.S, buf.sg, buf.workspace_shared,
+                           shared_policy)
+    moe_combine(buf.Yp, buf.row_of_pair, buf.topk_w, buf.S, buf.sg, buf.out)
+    return buf

@@ -1,0 +1,176 @@
+// C entry points of the MoE-layer library: argument checks and the choice of kernel shapes.
+// Semantics of every call are stated in include/moe.h.
+#include "../../include/moe.h"
+#include "common.h"
+
+using namespace moe;
+
+namespace {
+
+size_t align256(size_t n) { return (n + 255) & ~(size_t)255; }
+
+bool dims_ok(int H) { return H > 0 && H % 64 == 0; }
+
+// Which kernels serve an FFN with `mean_rows` expected rows per expert.  The choice uses only
+// layer-wide sizes (never the block bounds), so a row's result does not depend on the block cut.
+// policy: 0 = automatic; 1 = streaming, no K split; 2 = streaming, K split over 4 waves;
+//         3 = MFMA tiles of 128 rows; 4 = MFMA tiles of 256 rows.
+// Bits 8 and 9 of the policy word restrict a call to one of its two kernels (0x100: gate/up
+// only, 0x200: down projection only), so that each can be timed on its own.
+struct Plan { bool stream; int ksplit; int tile_rows; bool do_gateup; bool do_down; };
+Plan make_plan(int mean_rows, int n_experts_layer, int policy_word) {
+  Plan p{};
+  const int phase = (policy_word >> 8) & 3;
+  const int policy = policy_word & 0xff;
+  p.do_gateup = phase == 0 || (phase & 1);
+  p.do_down = phase == 0 || (phase & 2);
+  switch (policy) {
+    case 1: p.stream = true; p.ksplit = 1; return p;
+    case 2: p.stream = true; p.ksplit = 4; return p;
+    case 3: p.stream = false; p.tile_rows = 128; return p;
+    case 4: p.stream = false; p.tile_rows = 256; return p;
+    default: break;
+  }
+  if (mean_rows <= 48) {
+    p.stream = true;
+    p.ksplit = n_experts_layer >= 16 ? 1 : 4;   // few experts: split K to get enough waves
+  } else {
+    p.stream = false;
+    p.tile_rows = mean_rows >= 1024 ? 256 : 128;
+  }
+  return p;
+}
+
+int ffn_forward(const GemmArgs& gu, const GemmArgs& dn, const Plan& p, hipStream_t st) {
+  int rc = 0;
+  if (p.stream) {
+    if (p.do_gateup && (rc = launch_stream_gateup(gu, p.ksplit, st)) != 0) return rc;
+    if (p.do_down) rc = launch_stream_down(dn, p.ksplit, st);
+    return rc;
+  }
+  if (p.do_gateup && (rc = launch_tile_gateup(gu, p.tile_rows, st)) != 0) return rc;
+  if (p.do_down) rc = launch_tile_down(dn, p.tile_rows, st);
+  return rc;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* moe_status_string(int status) {
+  switch (status) {
+    case MOE_OK: return "ok";
+    case MOE_ERR_NULL: return "a required pointer is NULL";
+    case MOE_ERR_SHAPE: return "a size or an expert range is outside the supported limits";
+    case MOE_ERR_WORKSPACE: return "workspace too small";
+    case MOE_ERR_LAUNCH: return "kernel launch failed";
+    default: return "unknown status";
+  }
+}
+
+size_t moe_permute_workspace_bytes(int T, int K, int E) {
+  (void)T; (void)K; (void)E;
+  return 0;
+}
+size_t moe_expert_workspace_bytes(int P, int I) {
+  if (P <= 0 || I <= 0) return 0;
+  return align256((size_t)P * (size_t)I * 2);
+}
+size_t moe_shared_workspace_bytes(int T, int Is) {
+  if (T <= 0 || Is <= 0) return 0;
+  return align256((size_t)T * (size_t)Is * 2);
+}
+size_t moe_workspace_bytes(int T, int H, int E, int K, int I, int Is) {
+  (void)H;
+  size_t a = moe_permute_workspace_bytes(T, K, E);
+  size_t b = moe_expert_workspace_bytes(T * K, I);
+  size_t c = moe_shared_workspace_bytes(T, Is);
+  size_t m = a > b ? a : b;
+  return m > c ? m : c;
+}
+
+int moe_route(const void* x, const void* Wr, const float* bias, int T, int H, int E, int K, int renorm,
+              int32_t* topk_ids, float* topk_w, void* stream) {
+  if (T < 0 || !dims_ok(H) || H > 8192 || E < 1 || E > 256 || K < 1 || K > 16 || K > E) return MOE_ERR_SHAPE;
+  if (T == 0) return MOE_OK;
+  if (!x || !Wr || !topk_ids || !topk_w) return MOE_ERR_NULL;
+  return launch_route(x, Wr, bias, T, H, E, K, renorm, topk_ids, topk_w, (hipStream_t)stream);
+}
+
+int moe_permute(const int32_t* topk_ids, const void* x, int T, int H, int E, int K, int32_t* expert_offsets,
+                int32_t* src_of_row, int32_t* row_of_pair, void* Xp, void* workspace, size_t workspace_bytes,
+                void* stream) {
+  (void)workspace; (void)workspace_bytes;
+  if (T < 0 || !dims_ok(H) || E < 1 || E > 256 || K < 1 || K > 16 || K > E) return MOE_ERR_SHAPE;
+  if ((long long)T * K * H >= (1ll << 31)) return MOE_ERR_SHAPE;
+  if (!expert_offsets) return MOE_ERR_NULL;
+  if (T > 0 && (!topk_ids || !x || !src_of_row || !row_of_pair || !Xp)) return MOE_ERR_NULL;
+  return launch_permute(topk_ids, x, T, H, E, K, expert_offsets, src_of_row, row_of_pair, Xp, (hipStream_t)stream);
+}
+
+int moe_expert_group_forward_ex(int group_lo, int group_hi, const void* Xp, const int32_t* expert_offsets,
+                                const void* Wg, const void* Wu, const void* Wd, int P, int H, int E, int I,
+                                void* Yp, void* workspace, size_t workspace_bytes, int policy, void* stream) {
+  if (P < 0 || !dims_ok(H) || !dims_ok(I) || E < 1 || E > 256) return MOE_ERR_SHAPE;
+  if (group_lo < 0 || group_hi > E || group_lo >= group_hi) return MOE_ERR_SHAPE;
+  if ((long long)P * (H > I ? H : I) >= (1ll << 31)) return MOE_ERR_SHAPE;
+  if (P == 0) return MOE_OK;
+  if (!Xp || !expert_offsets || !Wg || !Wu || !Wd || !Yp || !workspace) return MOE_ERR_NULL;
+  if (workspace_bytes < (size_t)P * (size_t)I * 2) return MOE_ERR_WORKSPACE;   // h, bf16 [P,I]
+  const int mean_rows = (P + E - 1) / E;
+  const Plan plan = make_plan(mean_rows, E, policy);
+  GemmArgs gu{};
+  gu.A = (const bf16_t*)Xp; gu.B0 = (const bf16_t*)Wg; gu.B1 = (const bf16_t*)Wu; gu.C = (bf16_t*)workspace;
+  gu.offsets = expert_offsets; gu.lo = group_lo; gu.hi = group_hi; gu.rows_fixed = 0; gu.rows_total = P;
+  gu.mean_rows = mean_rows; gu.N = I; gu.Kdim = H;
+  GemmArgs dn = gu;
+  dn.A = (const bf16_t*)workspace; dn.B0 = (const bf16_t*)Wd; dn.B1 = nullptr; dn.C = (bf16_t*)Yp;
+  dn.N = H; dn.Kdim = I;
+  return ffn_forward(gu, dn, plan, (hipStream_t)stream);
+}
+
+int moe_expert_group_forward(int group_lo, int group_hi, const void* Xp, const int32_t* expert_offsets,
+                             const void* Wg, const void* Wu, const void* Wd, int P, int H, int E, int I, void* Yp,
+                             void* workspace, size_t workspace_bytes, void* stream) {
+  return moe_expert_group_forward_ex(group_lo, group_hi, Xp, expert_offsets, Wg, Wu, Wd, P, H, E, I, Yp, workspace,
+                                     workspace_bytes, 0, stream);
+}
+
+int moe_shared_forward_ex(const void* x, const void* Wsg, const void* Wsu, const void* Wsd, const void* wgate, int T,
+                          int H, int Is, void* S, float* sg, void* workspace, size_t workspace_bytes, int policy,
+                          void* stream) {
+  if (T < 0 || !dims_ok(H) || !dims_ok(Is)) return MOE_ERR_SHAPE;
+  if ((long long)T * (H > Is ? H : Is) >= (1ll << 31)) return MOE_ERR_SHAPE;
+  if (T == 0) return MOE_OK;
+  if (!x || !Wsg || !Wsu || !Wsd || !S || !workspace) return MOE_ERR_NULL;
+  if (wgate && !sg) return MOE_ERR_NULL;
+  if (workspace_bytes < (size_t)T * (size_t)Is * 2) return MOE_ERR_WORKSPACE;   // h, bf16 [T,Is]
+  const Plan plan = make_plan(T, 1, policy);
+  GemmArgs gu{};
+  gu.A = (const bf16_t*)x; gu.B0 = (const bf16_t*)Wsg; gu.B1 = (const bf16_t*)Wsu; gu.C = (bf16_t*)workspace;
+  gu.offsets = nullptr; gu.lo = 0; gu.hi = 1; gu.rows_fixed = T; gu.rows_total = T; gu.mean_rows = T;
+  gu.N = Is; gu.Kdim = H;
+  GemmArgs dn = gu;
+  dn.A = (const bf16_t*)workspace; dn.B0 = (const bf16_t*)Wsd; dn.B1 = nullptr; dn.C = (bf16_t*)S;
+  dn.N = H; dn.Kdim = Is;
+  int rc = ffn_forward(gu, dn, plan, (hipStream_t)stream);
+  if (rc != 0) return rc;
+  if (wgate && plan.do_down) return launch_gate_dot(x, wgate, T, H, sg, (hipStream_t)stream);
+  return MOE_OK;
+}
+
+int moe_shared_forward(const void* x, const void* Wsg, const void* Wsu, const void* Wsd, const void* wgate, int T,
+                       int H, int Is, void* S, float* sg, void* workspace, size_t workspace_bytes, void* stream) {
+  return moe_shared_forward_ex(x, Wsg, Wsu, Wsd, wgate, T, H, Is, S, sg, workspace, workspace_bytes, 0, stream);
+}
+
+int moe_combine(const void* Yp, const int32_t* row_of_pair, const float* topk_w, const void* S, const float* sg,
+                int T, int H, int K, void* out, void* stream) {
+  if (T < 0 || !dims_ok(H) || K < 1 || K > 16) return MOE_ERR_SHAPE;
+  if (T == 0) return MOE_OK;
+  if (!Yp || !row_of_pair || !topk_w || !out) return MOE_ERR_NULL;
+  if ((S == nullptr) != (sg == nullptr)) return MOE_ERR_NULL;
+  return launch_combine(Yp, row_of_pair, topk_w, S, sg, T, H, K, out, (hipStream_t)stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,91 @@
+// Aggregation (FaaSMoE Sec. 3 and Sec. 4.2: the orchestrator aggregates what the expert blocks
+// return).  out[t,:] = sum_j topk_w[t,j] * Yp[row_of_pair[t*K+j],:] + sigmoid(sg[t]) * S[t,:].
+//
+// A gather, not a scatter: one workgroup per token reads its K expert rows (and the shared
+// row) with 16-byte loads, accumulates in fp32 in slot order j = 0..K-1 and rounds once to
+// bf16.  No atomics, so the result does not depend on which block produced a row or when.
+#include "common.h"
+
+namespace moe {
+
+constexpr int COMBINE_KMAX = 16;
+
+__global__ __launch_bounds__(256) void combine_kernel(const bf16_t* __restrict__ Yp,
+                                                      const int32_t* __restrict__ row_of_pair,
+                                                      const float* __restrict__ topk_w,
+                                                      const bf16_t* __restrict__ S, const float* __restrict__ sg,
+                                                      int H, int K, bf16_t* __restrict__ out) {
+  const int t = blockIdx.x;
+  __shared__ int s_row[COMBINE_KMAX];
+  __shared__ float s_w[COMBINE_KMAX];
+  if (threadIdx.x < K) {
+    s_row[threadIdx.x] = row_of_pair[(size_t)t * K + threadIdx.x];
+    s_w[threadIdx.x] = topk_w[(size_t)t * K + threadIdx.x];
+  }
+  __syncthreads();
+  float gate = 0.0f;
+  if (S != nullptr) gate = 1.0f / (1.0f + expf(-sg[t]));
+
+  for (int c = threadIdx.x; c < H / 8; c += 256) {
+    float acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i] = 0.0f;
+    for (int j = 0; j < K; ++j) {
+      const uint4 v = reinterpret_cast<const uint4*>(Yp + (size_t)s_row[j] * H)[c];
+      const float wj = s_w[j];
+      acc[0] = __builtin_fmaf(wj, bf16_lo(v.x), acc[0]); acc[1] = __builtin_fmaf(wj, bf16_hi(v.x), acc[1]);
+      acc[2] = __builtin_fmaf(wj, bf16_lo(v.y), acc[2]); acc[3] = __builtin_fmaf(wj, bf16_hi(v.y), acc[3]);
+      acc[4] = __builtin_fmaf(wj, bf16_lo(v.z), acc[4]); acc[5] = __builtin_fmaf(wj, bf16_hi(v.z), acc[5]);
+      acc[6] = __builtin_fmaf(wj, bf16_lo(v.w), acc[6]); acc[7] = __builtin_fmaf(wj, bf16_hi(v.w), acc[7]);
+    }
+    if (S != nullptr) {
+      const uint4 v = reinterpret_cast<const uint4*>(S + (size_t)t * H)[c];
+      acc[0] = __builtin_fmaf(gate, bf16_lo(v.x), acc[0]); acc[1] = __builtin_fmaf(gate, bf16_hi(v.x), acc[1]);
+      acc[2] = __builtin_fmaf(gate, bf16_lo(v.y), acc[2]); acc[3] = __builtin_fmaf(gate, bf16_hi(v.y), acc[3]);
+      acc[4] = __builtin_fmaf(gate, bf16_lo(v.z), acc[4]); acc[5] = __builtin_fmaf(gate, bf16_hi(v.z), acc[5]);
+      acc[6] = __builtin_fmaf(gate, bf16_lo(v.w), acc[6]); acc[7] = __builtin_fmaf(gate, bf16_hi(v.w), acc[7]);
+    }
+    uint4 o;
+    o.x = pack_bf16x2(acc[0], acc[1]);
+    o.y = pack_bf16x2(acc[2], acc[3]);
+    o.z = pack_bf16x2(acc[4], acc[5]);
+    o.w = pack_bf16x2(acc[6], acc[7]);
+    reinterpret_cast<uint4*>(out + (size_t)t * H)[c] = o;
+  }
+}
+
+// sg[t] = <x[t,:], wgate>: one wave per token, fp32.
+__global__ __launch_bounds__(256) void gate_dot_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ wgate,
+                                                       int T, int H, float* __restrict__ sg) {
+  const int lane = threadIdx.x & 63;
+  const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (t >= T) return;
+  float a = 0.0f;
+  for (int c = lane; c < H / 8; c += 64) {
+    const uint4 v = reinterpret_cast<const uint4*>(x + (size_t)t * H)[c];
+    const uint4 g = reinterpret_cast<const uint4*>(wgate)[c];
+    a = __builtin_fmaf(bf16_lo(v.x), bf16_lo(g.x), a); a = __builtin_fmaf(bf16_hi(v.x), bf16_hi(g.x), a);
+    a = __builtin_fmaf(bf16_lo(v.y), bf16_lo(g.y), a); a = __builtin_fmaf(bf16_hi(v.y), bf16_hi(g.y), a);
+    a = __builtin_fmaf(bf16_lo(v.z), bf16_lo(g.z), a); a = __builtin_fmaf(bf16_hi(v.z), bf16_hi(g.z), a);
+    a = __builtin_fmaf(bf16_lo(v.w), bf16_lo(g.w), a); a = __builtin_fmaf(bf16_hi(v.w), bf16_hi(g.w), a);
+  }
+  a = wave_sum(a);
+  if (lane == 0) sg[t] = a;
+}
+
+int launch_combine(const void* Yp, const int32_t* row_of_pair, const float* w, const void* S, const float* sg,
+                   int T, int H, int K, void* out, hipStream_t st) {
+  if (T == 0) return 0;
+  hipLaunchKernelGGL(combine_kernel, dim3(T), dim3(256), 0, st, (const bf16_t*)Yp, row_of_pair, w,
+                     (const bf16_t*)S, sg, H, K, (bf16_t*)out);
+  return hipGetLastError() == hipSuccess ? 0 : -4;
+}
+
+int launch_gate_dot(const void* x, const void* wgate, int T, int H, float* sg, hipStream_t st) {
+  if (T == 0) return 0;
+  hipLaunchKernelGGL(gate_dot_kernel, dim3((T + 3) / 4), dim3(256), 0, st, (const bf16_t*)x, (const bf16_t*)wgate,
+                     T, H, sg);
+  return hipGetLastError() == hipSuccess ? 0 : -4;
+}
+
+}  // namespace moe

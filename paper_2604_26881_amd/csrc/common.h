@@ -1,0 +1,70 @@
+// Shared device helpers for the gfx950 MoE-layer kernels (wave64, CDNA4).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace moe {
+
+typedef uint16_t bf16_t;  // raw bf16 bits
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;   // 16 bytes moved as one register quad
+
+constexpr int WAVE = 64;
+
+__device__ __forceinline__ float bf16_lo(uint32_t packed) { return __uint_as_float(packed << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t packed) { return __uint_as_float(packed & 0xffff0000u); }
+
+// fp32 -> bf16, round to nearest even (finite inputs).
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
+}
+
+__device__ __forceinline__ bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int s = 32; s >= 1; s >>= 1) v += __shfl_xor(v, s, WAVE);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int s = 32; s >= 1; s >>= 1) v = fmaxf(v, __shfl_xor(v, s, WAVE));
+  return v;
+}
+
+// Launch helpers used by the C entry points.
+struct GemmArgs {
+  const bf16_t* A;     // token rows [rows, Kdim]
+  const bf16_t* B0;    // weights [E, N, Kdim]  (gate branch, or the down projection)
+  const bf16_t* B1;    // weights of the up branch (gate/up kernels), else unused
+  bf16_t* C;           // output rows [rows, N]
+  const int32_t* offsets;  // expert_offsets on the device, or nullptr for one expert on rows [0, rows_fixed)
+  int lo, hi;          // experts [lo, hi)
+  int rows_fixed;
+  int rows_total;      // number of rows of A and C (upper bound used to size the grid)
+  int mean_rows;       // expected rows per expert (rows_total / experts of the layer): picks kernel shapes
+  int N;               // output columns (per branch for gate/up)
+  int Kdim;            // contraction length
+};
+
+int launch_route(const void* x, const void* Wr, const float* bias, int T, int H, int E, int K, int renorm,
+                 int32_t* ids, float* w, hipStream_t st);
+int launch_permute(const int32_t* ids, const void* x, int T, int H, int E, int K, int32_t* offsets,
+                   int32_t* src_of_row, int32_t* row_of_pair, void* Xp, hipStream_t st);
+int launch_combine(const void* Yp, const int32_t* row_of_pair, const float* w, const void* S, const float* sg,
+                   int T, int H, int K, void* out, hipStream_t st);
+int launch_gate_dot(const void* x, const void* wgate, int T, int H, float* sg, hipStream_t st);
+// Tiled MFMA kernels (many rows per expert) and streaming kernels (few rows per expert).
+int launch_tile_gateup(const GemmArgs& a, int tile_rows, hipStream_t st);
+int launch_tile_down(const GemmArgs& a, int tile_rows, hipStream_t st);
+int launch_stream_gateup(const GemmArgs& a, int ksplit, hipStream_t st);
+int launch_stream_down(const GemmArgs& a, int ksplit, hipStream_t st);
+
+}  // namespace moe

@@ -1,0 +1,77 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, sizes its workspaces as documented and rejects bad arguments before any launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    import paper_2604_26881_amd as moe
+    return moe.load()
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "moe.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(moe_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_symbols()
+    assert {"moe_route", "moe_permute", "moe_expert_group_forward", "moe_combine"} <= set(names)
+    for n in names:
+        assert getattr(lib, n) is not None, n
+    from paper_2604_26881_amd import binding
+    assert sorted(binding.SYMBOLS) == names
+
+
+def test_status_strings(lib):
+    for code in (0, -1, -2, -3, -4, -99):
+        s = lib.moe_status_string(code)
+        assert isinstance(s, bytes) and len(s) > 0
+
+
+def test_workspace_sizes(lib):
+    P, I, T, Is = 16384, 1408, 4096, 5632
+    assert lib.moe_expert_workspace_bytes(P, I) == P * I * 2
+    assert lib.moe_shared_workspace_bytes(T, Is) == T * Is * 2
+    assert lib.moe_expert_workspace_bytes(3, 64) % 256 == 0 and lib.moe_expert_workspace_bytes(3, 64) >= 3 * 64 * 2
+    assert lib.moe_workspace_bytes(T, 2048, 60, 4, I, Is) == max(P * I * 2, T * Is * 2)
+    assert lib.moe_expert_workspace_bytes(0, 64) == 0
+
+
+def test_bad_arguments_are_rejected_before_any_launch(lib):
+    p = ctypes.c_void_p(0x1000)   # never dereferenced on the host; no launch happens on these paths
+    SHAPE, NULL, WS = -2, -1, -3
+    # route
+    assert lib.moe_route(p, p, None, 4, 63, 8, 2, 0, p, p, None) == SHAPE     # H not a multiple of 64
+    assert lib.moe_route(p, p, None, 4, 64, 8, 9, 0, p, p, None) == SHAPE     # K > E
+    assert lib.moe_route(p, p, None, 4, 64, 300, 2, 0, p, p, None) == SHAPE   # E > 256
+    assert lib.moe_route(p, p, None, -1, 64, 8, 2, 0, p, p, None) == SHAPE
+    assert lib.moe_route(None, p, None, 4, 64, 8, 2, 0, p, p, None) == NULL
+    assert lib.moe_route(None, None, None, 0, 64, 8, 2, 0, None, None, None) == 0   # T = 0: no-op
+    # permute
+    assert lib.moe_permute(p, p, 4, 64, 8, 2, None, p, p, p, None, 0, None) == NULL
+    assert lib.moe_permute(p, p, 4, 60, 8, 2, p, p, p, p, None, 0, None) == SHAPE
+    # expert block: range checks
+    args = (p, p, p, p, p, 32, 64, 8, 128, p, p, 32 * 128 * 2, None)
+    assert lib.moe_expert_group_forward(3, 3, *args) == SHAPE      # empty range
+    assert lib.moe_expert_group_forward(-1, 3, *args) == SHAPE
+    assert lib.moe_expert_group_forward(0, 9, *args) == SHAPE      # hi > E
+    assert lib.moe_expert_group_forward(0, 8, p, p, p, p, p, 32, 64, 8, 100, p, p, 1 << 20, None) == SHAPE
+    assert lib.moe_expert_group_forward(0, 8, p, None, p, p, p, 32, 64, 8, 128, p, p, 1 << 20, None) == NULL
+    assert lib.moe_expert_group_forward(0, 8, p, p, p, p, p, 32, 64, 8, 128, p, p, 100, None) == WS
+    assert lib.moe_expert_group_forward(0, 8, None, None, None, None, None, 0, 64, 8, 128, None, None, 0, None) == 0
+    # shared expert
+    assert lib.moe_shared_forward(p, p, p, p, p, 4, 64, 96, p, p, p, 1 << 20, None) == SHAPE
+    assert lib.moe_shared_forward(p, p, p, p, p, 4, 64, 128, p, None, p, 1 << 20, None) == NULL
+    assert lib.moe_shared_forward(p, p, p, p, p, 4, 64, 128, p, p, p, 8, None) == WS
+    # combine
+    assert lib.moe_combine(p, p, p, p, None, 4, 64, 2, p, None) == NULL      # S without sg
+    assert lib.moe_combine(p, p, p, None, None, 4, 64, 17, p, None) == SHAPE
+    assert lib.moe_combine(None, p, p, None, None, 4, 64, 2, p, None) == NULL

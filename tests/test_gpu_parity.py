@@ -1,0 +1,339 @@
+"""Parity of the HIP path with the CPU oracle, on a real MI355X, through the C ABI.
+
+Integer results (expert ids, offsets, permutation, gathered rows) must match bit for bit.
+Floating-point results must satisfy, with g the GPU value and r the float64 oracle value,
+    max|g - r| / max|r| <= 2e-2            (normalised maximum error, the stated bound)
+and elementwise |g - r| <= 2e-2*|r| + 2e-2*rms(r).
+The expected error is far smaller: the GPU keeps fp32 accumulators and rounds h, Yp, S and out to
+bf16 once each (relative 2^-9 per rounding), so the tests also assert a 6e-3 normalised bound.
+"""
+import numpy as np
+import pytest
+import torch
+
+import workloads
+
+pytestmark = pytest.mark.gpu
+
+REL = 2e-2
+
+
+@pytest.fixture(scope="module")
+def moe():
+    import paper_2604_26881_amd as m
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    m.load()
+    return m
+
+
+def check_close(g, r, what, tight=6e-3):
+    g = g.astype(np.float64)
+    scale = np.abs(r).max()
+    rms = np.sqrt(np.mean(r * r))
+    err = np.abs(g - r)
+    nrm = err.max() / scale if scale > 0 else err.max()
+    print(f"[parity] {what}: normalised max err {nrm:.3e} (bound {REL:.0e}), rms(ref) {rms:.3e}", flush=True)
+    assert nrm <= REL, f"{what}: normalised max error {nrm}"
+    assert np.all(err <= REL * np.abs(r) + REL * rms), f"{what}: elementwise bound violated"
+    assert nrm <= tight, f"{what}: error {nrm} is inside the bound but larger than the arithmetic explains"
+
+
+def shared_of(d):
+    return None if d["Wsg"] is None else (d["Wsg"], d["Wsu"], d["Wsd"], d["wgate"])
+
+
+def gpu_shared(w):
+    return None if w.Wsg is None else (w.Wsg, w.Wsu, w.Wsd, w.wgate)
+
+
+def run_layer(moe, wl, groups=None, policy=0, shared_policy=0):
+    g = wl.to("cuda")
+    s = wl.shape
+    buf = moe.moe_layer_forward(g.x, g.Wr, g.bias, g.Wg, g.Wu, g.Wd, gpu_shared(g), s.K, s.renorm, groups=groups,
+                                tenant_rows=wl.tenant_rows, policy=policy, shared_policy=shared_policy)
+    torch.cuda.synchronize()
+    return buf
+
+
+def f64(t):
+    return t.float().cpu().numpy().astype(np.float64)
+
+
+# ------------------------------------------------------------------------------ gating
+
+ROUTE_CASES = [
+    # T, H, E, K, renorm, bias
+    (16, 64, 8, 2, False, False), (16, 64, 8, 2, True, True), (128, 2048, 60, 4, False, False),
+    (4096, 2048, 60, 4, False, True), (2049, 1024, 60, 4, True, True), (33, 512, 256, 8, False, True),
+    (5, 4096, 64, 16, True, False), (3, 8192, 7, 7, False, True), (1, 64, 1, 1, True, False),
+    (70, 1536, 130, 6, False, True),
+]
+
+
+@pytest.mark.parametrize("T,H,E,K,renorm,with_bias", ROUTE_CASES)
+def test_route_ids_bit_exact(moe, oracle64, T, H, E, K, renorm, with_bias):
+    print(f"[case] route T={T} H={H} E={E} K={K} renorm={renorm} bias={with_bias}", flush=True)
+    g = torch.Generator().manual_seed(T * 131 + E)
+    x = torch.randn((T, H), generator=g).to(torch.bfloat16)
+    Wr = (torch.randn((E, H), generator=g) * 0.02).to(torch.bfloat16)
+    bias = torch.randn((E,), generator=g) if with_bias else None
+    ids_ref, w_ref = oracle64.route(x.float().numpy(), Wr.float().numpy(), None if bias is None else bias.numpy(),
+                                    K, renorm)
+    ids, w = moe.moe_route(x.cuda(), Wr.cuda(), None if bias is None else bias.cuda(), K, renorm)
+    torch.cuda.synchronize()
+    assert np.array_equal(ids.cpu().numpy(), ids_ref)
+    assert np.allclose(w.cpu().numpy(), w_ref, rtol=2e-5, atol=1e-9)
+
+
+def test_route_ties_go_to_the_lower_id(moe, oracle64):
+    T, H, E, K = 9, 128, 60, 4
+    g = torch.Generator().manual_seed(5)
+    x = torch.randn((T, H), generator=g).to(torch.bfloat16)
+    Wr = torch.zeros((E, H), dtype=torch.bfloat16)
+    ids, w = moe.moe_route(x.cuda(), Wr.cuda(), None, K, False)
+    assert np.array_equal(ids.cpu().numpy(), np.tile(np.arange(K, dtype=np.int32), (T, 1)))
+    assert np.allclose(w.cpu().numpy(), 1.0 / E, rtol=1e-6)
+    # duplicated router rows and integer-valued biases: many exact ties, the oracle decides
+    Wr = (torch.randn((E, H), generator=g) * 0.02).to(torch.bfloat16)
+    Wr[7] = Wr[3]
+    Wr[40] = Wr[3]
+    Wr[41] = Wr[50]
+    bias = torch.randint(-1, 2, (E,), generator=g).float()
+    Wr[10:20] = 0
+    ids_ref, w_ref = oracle64.route(x.float().numpy(), Wr.float().numpy(), bias.numpy(), 8, True)
+    ids, w = moe.moe_route(x.cuda(), Wr.cuda(), bias.cuda(), 8, True)
+    assert np.array_equal(ids.cpu().numpy(), ids_ref)
+    assert np.allclose(w.cpu().numpy(), w_ref, rtol=2e-5)
+    assert np.allclose(w.cpu().numpy().sum(axis=1), 1.0, atol=1e-5)
+
+
+def test_route_slices_equal_the_whole(moe):
+    wl = workloads.tenants(seed=3, n_tenants=4, T_per=64, I=64, Is=0).to("cuda")
+    ids_all, w_all = moe.moe_route(wl.x, wl.Wr, wl.bias[1], 4, False)
+    ids_s, w_s = moe.moe_route(wl.x[64:128], wl.Wr, wl.bias[1], 4, False)
+    torch.cuda.synchronize()
+    assert torch.equal(ids_all[64:128], ids_s) and torch.equal(w_all[64:128], w_s)
+
+
+# ------------------------------------------------------------------------------ permutation
+
+@pytest.mark.parametrize("T,H,E,K", [(16, 64, 8, 2), (128, 2048, 60, 4), (4096, 2048, 60, 4), (1, 64, 4, 4),
+                                      (300, 128, 7, 3), (0, 64, 5, 2), (40000, 64, 256, 4), (9000, 64, 60, 16),
+                                      (777, 192, 130, 5)])
+def test_permute_bit_exact(moe, oracle64, T, H, E, K):
+    print(f"[case] permute T={T} H={H} E={E} K={K}", flush=True)
+    rng = np.random.default_rng(T + 7 * E)
+    # skewed popularity so some experts are empty and some are large
+    pop = rng.random(E) ** 3 + 1e-3
+    if T > 0:
+        keys = rng.random((T, E)) ** (1.0 / pop)
+        ids = np.argsort(-keys, axis=1)[:, :K].astype(np.int32)
+    else:
+        ids = np.zeros((0, K), np.int32)
+    x = torch.randn((T, H), generator=torch.Generator().manual_seed(T)).to(torch.bfloat16)
+    off_r, src_r, rowp_r = oracle64.permute(ids, E)
+    off, src, rowp, Xp = moe.moe_permute(torch.from_numpy(ids).cuda(), x.cuda(), E)
+    torch.cuda.synchronize()
+    assert np.array_equal(off.cpu().numpy(), off_r)
+    assert np.array_equal(rowp.cpu().numpy(), rowp_r)
+    assert np.array_equal(src.cpu().numpy(), src_r)
+    if T > 0:
+        expect = x[torch.from_numpy(src_r.astype(np.int64)) // K]
+        assert torch.equal(Xp.cpu().view(torch.int16), expect.view(torch.int16))
+
+
+# ------------------------------------------------------------------------------ expert blocks
+
+def skewed_workload(T, H, E, K, I, Is, seed):
+    """Qwen-proportioned layer with a strong Zipf bias: a few experts get hundreds of rows, most get
+    a handful, some none, so one call covers full tiles, ragged tails and empty experts."""
+    return workloads.prefill(seed=seed, T=T, H=H, E=E, K=K, I=I, Is=Is)
+
+
+@pytest.mark.parametrize("policy", [0, 1, 2, 3, 4])
+def test_expert_blocks_match_oracle(moe, oracle64, policy):
+    wl = skewed_workload(T=700, H=256, E=20, K=4, I=192, Is=0, seed=21)
+    s = wl.shape
+    d = wl.f32_numpy()
+    ref = oracle64.layer(d["x"], d["Wr"], d["bias"], d["Wg"], d["Wu"], d["Wd"], None, s.K, s.renorm)
+    counts = np.diff(ref["offsets"])
+    print(f"[case] expert blocks policy={policy} rows/expert min {counts.min()} max {counts.max()}", flush=True)
+    assert counts.max() > 300 and counts.min() < 20
+    g = wl.to("cuda")
+    ids, w = moe.moe_route(g.x, g.Wr, g.bias, s.K, s.renorm)
+    off, src, rowp, Xp = moe.moe_permute(ids, g.x, s.E)
+    P = s.P
+    ws = torch.empty(P * s.I * 2, dtype=torch.uint8, device="cuda")
+    Yp = torch.full((P, s.H), 768.0, dtype=torch.bfloat16, device="cuda")
+    lo, hi = 3, 17
+    moe.moe_expert_group_forward(lo, hi, Xp, off, g.Wg, g.Wu, g.Wd, Yp, ws, policy)
+    torch.cuda.synchronize()
+    a, b = int(ref["offsets"][lo]), int(ref["offsets"][hi])
+    y = f64(Yp)
+    assert np.all(y[:a] == 768.0) and np.all(y[b:] == 768.0), "rows outside the block were written"
+    check_close(y[a:b], ref["Yp"][a:b], f"Yp rows of experts [{lo},{hi}) policy {policy}")
+    # the other experts, two more calls in reverse order; then the aggregation
+    moe.moe_expert_group_forward(hi, s.E, Xp, off, g.Wg, g.Wu, g.Wd, Yp, ws, policy)
+    moe.moe_expert_group_forward(0, lo, Xp, off, g.Wg, g.Wu, g.Wd, Yp, ws, policy)
+    out = moe.moe_combine(Yp, rowp, w, None, None)
+    torch.cuda.synchronize()
+    check_close(f64(Yp), ref["Yp"], f"Yp all rows policy {policy}")
+    check_close(f64(out), ref["out"], f"layer output policy {policy}")
+
+
+@pytest.mark.parametrize("policy", [0, 1, 2, 3, 4])
+@pytest.mark.parametrize("T", [5, 130, 300])
+def test_shared_expert_matches_oracle(moe, oracle64, policy, T):
+    wl = workloads.decode(seed=31, T=T, H=256, E=8, I=64, Is=448)
+    d = wl.f32_numpy()
+    S_ref, sg_ref = oracle64.shared_forward(d["x"], d["Wsg"], d["Wsu"], d["Wsd"], d["wgate"])
+    g = wl.to("cuda")
+    S = torch.empty((T, 256), dtype=torch.bfloat16, device="cuda")
+    sg = torch.empty(T, dtype=torch.float32, device="cuda")
+    ws = torch.empty(T * 448 * 2, dtype=torch.uint8, device="cuda")
+    moe.moe_shared_forward(g.x, g.Wsg, g.Wsu, g.Wsd, g.wgate, S, sg, ws, policy)
+    torch.cuda.synchronize()
+    check_close(f64(S), S_ref, f"shared expert T={T} policy {policy}")
+    assert np.allclose(sg.cpu().numpy(), sg_ref, rtol=1e-4, atol=1e-5)
+
+
+def test_combine_matches_oracle(moe, oracle64):
+    T, H, K = 50, 320, 3
+    g = torch.Generator().manual_seed(9)
+    Yp = torch.randn((T * K, H), generator=g).to(torch.bfloat16)
+    S = torch.randn((T, H), generator=g).to(torch.bfloat16)
+    sg = torch.randn((T,), generator=g)
+    w = torch.rand((T, K), generator=g)
+    rowp = torch.randperm(T * K, generator=g).to(torch.int32)
+    ref = oracle64.combine(Yp.float().numpy(), rowp.numpy(), w.numpy(), S.float().numpy(), sg.numpy(), K)
+    out = moe.moe_combine(Yp.cuda(), rowp.cuda(), w.cuda(), S.cuda(), sg.cuda())
+    check_close(f64(out), ref, "combine with shared", tight=4e-3)
+    ref = oracle64.combine(Yp.float().numpy(), rowp.numpy(), w.numpy(), None, None, K)
+    out = moe.moe_combine(Yp.cuda(), rowp.cuda(), w.cuda(), None, None)
+    check_close(f64(out), ref, "combine without shared", tight=4e-3)
+
+
+def test_stateless_and_deterministic(moe):
+    wl = skewed_workload(T=400, H=128, E=12, K=4, I=128, Is=128, seed=22)
+    a = run_layer(moe, wl, groups=workloads.partition(12, 5))
+    b = run_layer(moe, wl, groups=workloads.partition(12, 5)[::-1])
+    for name in ("topk_ids", "topk_w", "expert_offsets", "src_of_row", "row_of_pair", "Xp", "Yp", "S", "out"):
+        ta, tb = getattr(a, name), getattr(b, name)
+        assert torch.equal(ta.view(torch.uint8), tb.view(torch.uint8)), name
+
+
+# ------------------------------------------------------------------------------ whole layer
+
+def compare_layer(moe, oracle64, wl, groups=None, tight=6e-3):
+    s = wl.shape
+    d = wl.f32_numpy()
+    bias = d["bias"]
+    if wl.tenant_rows is not None:       # per-token bias: the oracle routes each tenant slice as well
+        refs = []
+        for i, (a, b) in enumerate(wl.tenant_rows):
+            refs.append(oracle64.route(d["x"][a:b], d["Wr"], bias[i], s.K, s.renorm))
+        ids_ref = np.concatenate([r[0] for r in refs])
+        w_ref = np.concatenate([r[1] for r in refs])
+    else:
+        ids_ref, w_ref = oracle64.route(d["x"], d["Wr"], bias, s.K, s.renorm)
+    off_r, src_r, rowp_r = oracle64.permute(ids_ref, s.E)
+    buf = run_layer(moe, wl, groups=groups)
+    assert np.array_equal(buf.topk_ids.cpu().numpy(), ids_ref)
+    assert np.allclose(buf.topk_w.cpu().numpy(), w_ref, rtol=2e-5)
+    assert np.array_equal(buf.expert_offsets.cpu().numpy(), off_r)
+    assert np.array_equal(buf.src_of_row.cpu().numpy(), src_r)
+    assert np.array_equal(buf.row_of_pair.cpu().numpy(), rowp_r)
+    return buf, dict(ids=ids_ref, w=w_ref, offsets=off_r, src_of_row=src_r, row_of_pair=rowp_r), d
+
+
+@pytest.mark.parametrize("renorm", [False, True])
+def test_tiny_layer(moe, oracle64, renorm):
+    # the tiny fp32 configuration, rounded once to bf16 and fed to both sides
+    wl = workloads.tiny(seed=0, renorm=renorm).to_bf16()
+    s = wl.shape
+    d = wl.f32_numpy()
+    ref = oracle64.layer(d["x"], d["Wr"], None, d["Wg"], d["Wu"], d["Wd"], None, s.K, renorm)
+    buf, _, _ = compare_layer(moe, oracle64, wl)
+    check_close(f64(buf.out), ref["out"], f"tiny layer renorm={renorm}")
+
+
+def test_decode_layer_full_size_every_element(moe, oracle64):
+    # T = 128 on the full Qwen-shaped layer: the oracle computes every element (about 18 GFLOP)
+    wl = workloads.decode()
+    s = wl.shape
+    buf, r, d = compare_layer(moe, oracle64, wl)
+    Xp = oracle64.gather(d["x"], r["src_of_row"], s.K)
+    Yp = oracle64.expert_group_forward(0, s.E, Xp, r["offsets"], d["Wg"], d["Wu"], d["Wd"])
+    S, sg = oracle64.shared_forward(d["x"], d["Wsg"], d["Wsu"], d["Wsd"], d["wgate"])
+    out = oracle64.combine(Yp, r["row_of_pair"], r["w"], S, sg, s.K)
+    check_close(f64(buf.Yp), Yp, "decode Yp")
+    check_close(f64(buf.S), S, "decode shared expert")
+    check_close(f64(buf.out), out, "decode layer output")
+
+
+def sample_tokens(T, n, seed):
+    rng = np.random.default_rng(seed)
+    tok = np.unique(np.concatenate([[0, T - 1], rng.integers(0, T, size=n)])).astype(np.int32)
+    return tok
+
+
+def test_prefill_layer_full_size_sampled_tokens(moe, oracle64):
+    # T = 4096 with Zipf-skewed routing, in the configuration the benchmark times: ids and the
+    # permutation are compared for every token, the output on sampled tokens the oracle computes
+    # one by one from the per-token definition.
+    wl = workloads.prefill()
+    s = wl.shape
+    buf, r, d = compare_layer(moe, oracle64, wl)
+    counts = np.diff(r["offsets"])
+    print(f"[case] prefill rows/expert: max {counts.max()} median {int(np.median(counts))} min {counts.min()}",
+          flush=True)
+    tok = sample_tokens(s.T, 22, 4)
+    ref, ids_t, _ = oracle64.token_forward(tok, d["x"], d["Wr"], d["bias"], d["Wg"], d["Wu"], d["Wd"], shared_of(d),
+                                           s.K, s.renorm)
+    assert np.array_equal(ids_t, r["ids"][tok])
+    check_close(f64(buf.out)[tok], ref, "prefill layer output on sampled tokens")
+
+
+def test_block_size_does_not_change_the_result_bitwise(moe, oracle64):
+    # 4 tenants x 512 tokens, each routed with its own bias, one permute over all 2048 tokens, the
+    # experts invoked as blocks of g experts: the output must be bit-identical for every g (Sec. 3)
+    wl = workloads.tenants()
+    s = wl.shape
+    outs = {}
+    for g in (60, 15, 4, 1, 20, 7):
+        buf = run_layer(moe, wl, groups=workloads.partition(s.E, g))
+        outs[g] = (buf.out.clone(), buf.Yp.clone())
+    for g in outs:
+        assert torch.equal(outs[g][0].view(torch.int16), outs[60][0].view(torch.int16)), f"out differs for g={g}"
+        assert torch.equal(outs[g][1].view(torch.int16), outs[60][1].view(torch.int16)), f"Yp differs for g={g}"
+    buf, r, d = compare_layer(moe, oracle64, wl, groups=workloads.partition(s.E, 15))
+    tok = sample_tokens(s.T, 10, 5)
+    refs = []
+    for t in tok:        # per-token bias of the token's tenant
+        ref, _, _ = oracle64.token_forward(np.array([t], np.int32), d["x"], d["Wr"], d["bias"][t // 512], d["Wg"],
+                                           d["Wu"], d["Wd"], shared_of(d), s.K, s.renorm)
+        refs.append(ref[0])
+    check_close(f64(buf.out)[tok], np.stack(refs), "multi-tenant layer output on sampled tokens")
+
+
+def test_empty_and_degenerate_inputs(moe, oracle64):
+    # every token to the same K experts: E - K experts are empty
+    wl = workloads.decode(seed=41, T=70, H=128, E=16, I=64, Is=0)
+    wl.bias = torch.zeros(16)
+    wl.bias[5] = 50.0
+    wl.bias[11] = 40.0
+    wl.bias[2] = 30.0
+    wl.bias[9] = 20.0
+    s = wl.shape
+    d = wl.f32_numpy()
+    ref = oracle64.layer(d["x"], d["Wr"], d["bias"], d["Wg"], d["Wu"], d["Wd"], None, s.K, s.renorm)
+    buf, _, _ = compare_layer(moe, oracle64, wl, groups=workloads.partition(16, 3))
+    assert np.array_equal(buf.topk_ids.cpu().numpy()[:, 0], np.full(70, 5))
+    check_close(f64(buf.out), ref["out"], "all tokens on four experts")
+    # K = E = 1 and a single token
+    wl = workloads.decode(seed=42, T=1, H=64, E=1, K=1, I=64, Is=64)
+    s = wl.shape
+    d = wl.f32_numpy()
+    ref = oracle64.layer(d["x"], d["Wr"], None, d["Wg"], d["Wu"], d["Wd"], shared_of(d), 1, False)
+    buf, _, _ = compare_layer(moe, oracle64, wl)
+    check_close(f64(buf.out), ref["out"], "one token, one expert")
