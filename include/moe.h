@@ -54,7 +54,7 @@ const char* moe_status_string(int status);
  *   topk_w[t,j] = p[t, topk_ids[t,j]], divided by their sum over j when renorm != 0
  * Summation order of the dot product: element h belongs to partial sum (h/8) mod 64; each
  * partial takes its elements in ascending h by fused multiply-add starting from +0; the 64
- * partials are folded by a butterfly a[j] += a[j xor s] for s = 32,16,8,4,2,1; the bias is added
+ * partials are folded by a butterfly a[j] += a[j xor s] for s = 1,2,4,8,16,32; the bias is added
  * last.  bf16 products are exact in fp32, so the logits are reproducible bit for bit.
  * Row t of the outputs depends on row t of x only, so slices of a batch (one per tenant, each
  * with its own bias) may be routed by separate calls.

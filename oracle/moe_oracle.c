@@ -30,7 +30,7 @@
  * Fixed order of the router dot product.  H must be a multiple of 8.  Element h belongs to
  * partial sum j = (h / 8) mod 64.  Each of the 64 partial sums starts at +0 and takes its
  * elements in ascending h with one fused multiply-add each.  The 64 partials are then folded by
- * a butterfly: for s = 32, 16, 8, 4, 2, 1 every partial j becomes a[j] + a[j xor s].  Addition
+ * a butterfly: for s = 1, 2, 4, 8, 16, 32 every partial j becomes a[j] + a[j xor s].  Addition
  * is commutative, so after the last stage all 64 hold the same value, which is the dot product.
  * The bias, if any, is added after that.
  *
@@ -82,7 +82,7 @@ static float router_dot(const float* x, const float* w, int H) {
     int j = (h >> 3) & 63;
     a[j] = fmaf(x[h], w[h], a[j]);
   }
-  for (int s = 32; s >= 1; s >>= 1) {
+  for (int s = 1; s <= 32; s <<= 1) {
     for (int j = 0; j < 64; ++j) b[j] = a[j] + a[j ^ s];
     memcpy(a, b, sizeof a);
   }

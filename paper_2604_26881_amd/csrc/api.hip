@@ -31,9 +31,10 @@ Plan make_plan(int mean_rows, int n_experts_layer, int policy_word) {
     case 4: p.stream = false; p.tile_rows = 256; return p;
     default: break;
   }
-  if (mean_rows <= 48) {
+  const bool few_experts = n_experts_layer < 16;   // e.g. the shared expert: one weight set, all rows
+  if (mean_rows <= (few_experts ? 128 : 48)) {
     p.stream = true;
-    p.ksplit = n_experts_layer >= 16 ? 1 : 4;   // few experts: split K to get enough waves
+    p.ksplit = few_experts ? 4 : 1;   // few experts: split K over the waves to get enough of them
   } else {
     p.stream = false;
     p.tile_rows = mean_rows >= 1024 ? 256 : 128;

@@ -193,8 +193,8 @@ static int launch_stream_t(const GemmArgs& a, hipStream_t st) {
 template <bool GATEUP>
 static int launch_stream_any(const GemmArgs& a, int ksplit, hipStream_t st) {
   // token tiles held in registers: sized for about twice the mean rows per expert
-  const int mean = a.mean_rows;
-  const int want = (2 * mean + 15) / 16;
+  // with expert_offsets the rows per expert vary around the mean: leave room for twice the mean
+  const int want = a.offsets ? (2 * a.mean_rows + 15) / 16 : (a.rows_fixed + 15) / 16;
   const int mt = want <= 1 ? 1 : (want <= 2 ? 2 : 4);
   if (ksplit > 1) {
     if (mt == 1) return launch_stream_t<1, 4, GATEUP>(a, st);

@@ -1,22 +1,55 @@
 // Gating kernel: router logits, softmax and top-k per token (FaaSMoE Sec. 2.1: the gating
 // network selects the top-k experts for each token; Sec. 3: it runs in the orchestrator).
 //
-// One workgroup of four waves serves TOK tokens.  The experts are dealt round-robin to the four
-// waves; a wave keeps the TOK token rows in registers as fp32, streams one router row at a time
-// and forms the dot product in the fixed order of the interface: lane j owns elements
-// 512*c + 8*j .. +7 of every 512-element chunk c (one 16-byte load per chunk), accumulates them
-// in ascending index by fused multiply-add, and the 64 lane sums are folded by an xor butterfly
-// 32,16,...,1.  bf16 products are exact in fp32, so this reproduces a CPU evaluation in the same
-// order bit for bit.  The logits meet in LDS; then one wave per token runs softmax and K rounds
-// of wave-wide argmax (ties to the lower expert id).
+// One workgroup of four waves serves TOK tokens.  The experts are dealt to the four waves EB at a
+// time; a wave keeps the TOK token rows in registers as fp32, streams EB router rows per step and
+// forms TOK*EB dot products at once (independent accumulator chains) in the fixed order of the
+// interface: lane j owns elements 512*c + 8*j .. +7 of every 512-element chunk c (one 16-byte
+// load per chunk) and accumulates them in ascending index by fused multiply-add; the 64 lane sums
+// are folded pairwise over lane strides 1, 2, 4, 8, 16, 32.  The fold runs on the VALU with DPP
+// lane selects: after the stride-1 and stride-2 steps the four lanes of a quad hold the same
+// value, so "the lane at xor 4" may be any lane of the neighbouring quad (row_half_mirror), and
+// likewise row_mirror for stride 8 and the row broadcasts for strides 16 and 32; fp32 addition is
+// commutative, so every pairing adds the same two numbers as the xor butterfly.  bf16 products
+// are exact in fp32, so a CPU evaluation in the same order reproduces the logits bit for bit.
+// The logits meet in LDS; then one wave per token runs softmax and K rounds of wave-wide argmax
+// (a max fold, then ballots over the lanes that hold the maximum: the lowest expert id wins).
 #include "common.h"
 
 namespace moe {
 
 constexpr int ROUTE_EMAX = 256;
-constexpr int ROUTE_KMAX = 16;
 
-template <int C, int TOK>
+template <int CTRL, int RMASK>
+__device__ __forceinline__ float dpp_or(float keep, float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(keep), __float_as_int(v), CTRL, RMASK, 0xF, false));
+}
+// Sum of the 64 lane values, pairing lanes at strides 1,2,4,8,16,32; every lane returns the total.
+__device__ __forceinline__ float fold_sum(float a) {
+  a = a + dpp_or<0xB1, 0xF>(0.0f, a);    // quad_perm [1,0,3,2]  : stride 1
+  a = a + dpp_or<0x4E, 0xF>(0.0f, a);    // quad_perm [2,3,0,1]  : stride 2
+  a = a + dpp_or<0x141, 0xF>(0.0f, a);   // row_half_mirror      : stride 4
+  a = a + dpp_or<0x140, 0xF>(0.0f, a);   // row_mirror           : stride 8
+  a = a + dpp_or<0x142, 0xA>(0.0f, a);   // row_bcast15 into rows 1 and 3 : stride 16
+  a = a + dpp_or<0x143, 0xC>(0.0f, a);   // row_bcast31 into rows 2 and 3 : stride 32
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(a), 63));
+}
+__device__ __forceinline__ float fold_max(float a) {
+  a = fmaxf(a, dpp_or<0xB1, 0xF>(a, a));
+  a = fmaxf(a, dpp_or<0x4E, 0xF>(a, a));
+  a = fmaxf(a, dpp_or<0x141, 0xF>(a, a));
+  a = fmaxf(a, dpp_or<0x140, 0xF>(a, a));
+  a = fmaxf(a, dpp_or<0x142, 0xA>(a, a));
+  a = fmaxf(a, dpp_or<0x143, 0xC>(a, a));
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(a), 63));
+}
+
+__device__ __forceinline__ void widen8(u32x4 v, float* f) {
+  f[0] = bf16_lo(v.x); f[1] = bf16_hi(v.x); f[2] = bf16_lo(v.y); f[3] = bf16_hi(v.y);
+  f[4] = bf16_lo(v.z); f[5] = bf16_hi(v.z); f[6] = bf16_lo(v.w); f[7] = bf16_hi(v.w);
+}
+
+template <int C, int TOK, int EB>
 __global__ __launch_bounds__(256) void route_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ Wr,
                                                     const float* __restrict__ bias, int T, int H, int E, int K,
                                                     int renorm, int32_t* __restrict__ ids, float* __restrict__ w) {
@@ -31,40 +64,53 @@ __global__ __launch_bounds__(256) void route_kernel(const bf16_t* __restrict__ x
 #pragma unroll
     for (int c = 0; c < C; ++c) {
       const int h = 512 * c + 8 * lane;
-      uint4 v = make_uint4(0, 0, 0, 0);
-      if (h < H && t0 + tk < T) v = *reinterpret_cast<const uint4*>(x + (size_t)(t0 + tk) * H + h);
-      xf[tk][c][0] = bf16_lo(v.x); xf[tk][c][1] = bf16_hi(v.x);
-      xf[tk][c][2] = bf16_lo(v.y); xf[tk][c][3] = bf16_hi(v.y);
-      xf[tk][c][4] = bf16_lo(v.z); xf[tk][c][5] = bf16_hi(v.z);
-      xf[tk][c][6] = bf16_lo(v.w); xf[tk][c][7] = bf16_hi(v.w);
+      u32x4 v = {0u, 0u, 0u, 0u};
+      if (h < H && t0 + tk < T) v = *reinterpret_cast<const u32x4*>(x + (size_t)(t0 + tk) * H + h);
+      widen8(v, xf[tk][c]);
     }
   }
 
-  for (int e = wave; e < E; e += 4) {
-    float wf[C][8];
+  for (int e0 = wave * EB; e0 < E; e0 += 4 * EB) {
+    u32x4 wr[EB][C];
 #pragma unroll
-    for (int c = 0; c < C; ++c) {
-      const int h = 512 * c + 8 * lane;
-      uint4 v = make_uint4(0, 0, 0, 0);
-      if (h < H) v = *reinterpret_cast<const uint4*>(Wr + (size_t)e * H + h);
-      wf[c][0] = bf16_lo(v.x); wf[c][1] = bf16_hi(v.x);
-      wf[c][2] = bf16_lo(v.y); wf[c][3] = bf16_hi(v.y);
-      wf[c][4] = bf16_lo(v.z); wf[c][5] = bf16_hi(v.z);
-      wf[c][6] = bf16_lo(v.w); wf[c][7] = bf16_hi(v.w);
-    }
-    const float b = bias ? bias[e] : 0.0f;
-#pragma unroll
-    for (int tk = 0; tk < TOK; ++tk) {
-      float a = 0.0f;
+    for (int i = 0; i < EB; ++i) {
+      const int e = min(e0 + i, E - 1);
 #pragma unroll
       for (int c = 0; c < C; ++c) {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) a = __builtin_fmaf(xf[tk][c][i], wf[c][i], a);
+        const int h = 512 * c + 8 * lane;
+        wr[i][c] = u32x4{0u, 0u, 0u, 0u};
+        if (h < H) wr[i][c] = *reinterpret_cast<const u32x4*>(Wr + (size_t)e * H + h);
       }
+    }
+    float a[EB][TOK];
 #pragma unroll
-      for (int s = 32; s >= 1; s >>= 1) a = a + __shfl_xor(a, s, WAVE);
-      if (bias) a = a + b;
-      if (lane == 0) s_logit[tk][e] = a;
+    for (int i = 0; i < EB; ++i)
+#pragma unroll
+      for (int tk = 0; tk < TOK; ++tk) a[i][tk] = 0.0f;
+#pragma unroll
+    for (int c = 0; c < C; ++c) {
+      float wf[EB][8];
+#pragma unroll
+      for (int i = 0; i < EB; ++i) widen8(wr[i][c], wf[i]);
+#pragma unroll
+      for (int k = 0; k < 8; ++k)
+#pragma unroll
+        for (int i = 0; i < EB; ++i)
+#pragma unroll
+          for (int tk = 0; tk < TOK; ++tk) a[i][tk] = __builtin_fmaf(xf[tk][c][k], wf[i][k], a[i][tk]);
+    }
+#pragma unroll
+    for (int i = 0; i < EB; ++i) {
+      const int e = e0 + i;
+      if (e < E) {
+        const float b = bias ? bias[e] : 0.0f;
+#pragma unroll
+        for (int tk = 0; tk < TOK; ++tk) {
+          float r = fold_sum(a[i][tk]);
+          if (bias) r = r + b;
+          if (lane == 0) s_logit[tk][e] = r;
+        }
+      }
     }
   }
   __syncthreads();
@@ -80,28 +126,27 @@ __global__ __launch_bounds__(256) void route_kernel(const bf16_t* __restrict__ x
       l[i] = e < E ? s_logit[tk][e] : -INFINITY;
       taken[i] = e >= E;
     }
-    const float m = wave_max(fmaxf(fmaxf(l[0], l[1]), fmaxf(l[2], l[3])));
+    const float m = fold_max(fmaxf(fmaxf(l[0], l[1]), fmaxf(l[2], l[3])));
     float z = 0.0f;
 #pragma unroll
     for (int i = 0; i < 4; ++i)
       if (lane + 64 * i < E) z += expf(l[i] - m);
-    const float denom = wave_sum(z);
+    const float denom = fold_sum(z);
 
     int my_id = 0;
     float my_w = 0.0f, run = 0.0f;
     for (int j = 0; j < K; ++j) {
       float bv = -INFINITY;
-      int be = 0x7fffffff;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {  // ascending expert id inside the lane: '>' keeps the lower id
-        if (!taken[i] && (be == 0x7fffffff || l[i] > bv)) { bv = l[i]; be = lane + 64 * i; }
-      }
+      for (int i = 0; i < 4; ++i)
+        if (!taken[i]) bv = fmaxf(bv, l[i]);
+      bv = fold_max(bv);
+      // lowest expert id among the untaken experts whose logit equals the maximum (-0 == +0)
+      int be = -1;
 #pragma unroll
-      for (int s = 32; s >= 1; s >>= 1) {
-        const float ov = __shfl_xor(bv, s, WAVE);
-        const int oe = __shfl_xor(be, s, WAVE);
-        const bool take = (oe != 0x7fffffff) && (be == 0x7fffffff || ov > bv || (ov == bv && oe < be));
-        if (take) { bv = ov; be = oe; }
+      for (int i = 0; i < 4; ++i) {
+        const unsigned long long hit = __ballot(!taken[i] && l[i] == bv);
+        if (be < 0 && hit != 0ull) be = __builtin_ctzll(hit) + 64 * i;
       }
 #pragma unroll
       for (int i = 0; i < 4; ++i)
@@ -118,12 +163,12 @@ __global__ __launch_bounds__(256) void route_kernel(const bf16_t* __restrict__ x
   }
 }
 
-template <int C, int TOK>
+template <int C, int TOK, int EB>
 static int launch_route_t(const void* x, const void* Wr, const float* bias, int T, int H, int E, int K, int renorm,
                           int32_t* ids, float* w, hipStream_t st) {
   const int blocks = (T + TOK - 1) / TOK;
-  hipLaunchKernelGGL((route_kernel<C, TOK>), dim3(blocks), dim3(256), 0, st, (const bf16_t*)x, (const bf16_t*)Wr,
-                     bias, T, H, E, K, renorm, ids, w);
+  hipLaunchKernelGGL((route_kernel<C, TOK, EB>), dim3(blocks), dim3(256), 0, st, (const bf16_t*)x,
+                     (const bf16_t*)Wr, bias, T, H, E, K, renorm, ids, w);
   return hipGetLastError() == hipSuccess ? 0 : -4;
 }
 
@@ -131,15 +176,15 @@ int launch_route(const void* x, const void* Wr, const float* bias, int T, int H,
                  int32_t* ids, float* w, hipStream_t st) {
   const int chunks = (H + 511) / 512;
   const bool many = T >= 2048;  // enough tokens to fill the chip with 4 per workgroup
-  if (chunks <= 1) return many ? launch_route_t<1, 4>(x, Wr, bias, T, H, E, K, renorm, ids, w, st)
-                               : launch_route_t<1, 1>(x, Wr, bias, T, H, E, K, renorm, ids, w, st);
-  if (chunks <= 2) return many ? launch_route_t<2, 4>(x, Wr, bias, T, H, E, K, renorm, ids, w, st)
-                               : launch_route_t<2, 1>(x, Wr, bias, T, H, E, K, renorm, ids, w, st);
-  if (chunks <= 4) return many ? launch_route_t<4, 4>(x, Wr, bias, T, H, E, K, renorm, ids, w, st)
-                               : launch_route_t<4, 1>(x, Wr, bias, T, H, E, K, renorm, ids, w, st);
-  if (chunks <= 8) return many ? launch_route_t<8, 2>(x, Wr, bias, T, H, E, K, renorm, ids, w, st)
-                               : launch_route_t<8, 1>(x, Wr, bias, T, H, E, K, renorm, ids, w, st);
-  if (chunks <= 16) return launch_route_t<16, 1>(x, Wr, bias, T, H, E, K, renorm, ids, w, st);
+  if (chunks <= 1) return many ? launch_route_t<1, 4, 2>(x, Wr, bias, T, H, E, K, renorm, ids, w, st)
+                               : launch_route_t<1, 1, 4>(x, Wr, bias, T, H, E, K, renorm, ids, w, st);
+  if (chunks <= 2) return many ? launch_route_t<2, 4, 2>(x, Wr, bias, T, H, E, K, renorm, ids, w, st)
+                               : launch_route_t<2, 1, 4>(x, Wr, bias, T, H, E, K, renorm, ids, w, st);
+  if (chunks <= 4) return many ? launch_route_t<4, 4, 2>(x, Wr, bias, T, H, E, K, renorm, ids, w, st)
+                               : launch_route_t<4, 1, 4>(x, Wr, bias, T, H, E, K, renorm, ids, w, st);
+  if (chunks <= 8) return many ? launch_route_t<8, 2, 2>(x, Wr, bias, T, H, E, K, renorm, ids, w, st)
+                               : launch_route_t<8, 1, 2>(x, Wr, bias, T, H, E, K, renorm, ids, w, st);
+  if (chunks <= 16) return launch_route_t<16, 1, 1>(x, Wr, bias, T, H, E, K, renorm, ids, w, st);
   return -2;
 }
 

@@ -107,6 +107,34 @@ def test_route_ties_go_to_the_lower_id(moe, oracle64):
     assert np.allclose(w.cpu().numpy().sum(axis=1), 1.0, atol=1e-5)
 
 
+def test_route_logits_bit_exact_through_cancelling_bias(moe, oracle64):
+    # The call returns no logits, so their bits are checked through the selection: with
+    # bias[e] = -L[t,e] (L = the oracle's fp32 logits of token t) every logit of token t is
+    # exactly +0 when the GPU's dot products have the oracle's bits, and the K lowest ids win the
+    # all-way tie; a single logit off by one ulp is the unique maximum (or, with Wr and the bias
+    # negated in a second call, the unique maximum there) and changes topk_ids.
+    g = torch.Generator().manual_seed(77)
+    for (T, H, E, K) in [(6, 2048, 60, 4), (4, 512, 256, 8), (4, 4096, 33, 16), (3, 8192, 20, 5), (4, 64, 8, 2)]:
+        print(f"[case] logits through bias T={T} H={H} E={E} K={K}", flush=True)
+        # wide dynamic range and random signs: the fp32 result depends strongly on the summation order
+        ex = torch.randint(-8, 9, (T, H), generator=g).float()
+        x = ((torch.randint(0, 2, (T, H), generator=g).float() * 2 - 1) * torch.pow(2.0, ex)
+             * (1 + torch.rand((T, H), generator=g))).to(torch.bfloat16)
+        Wr = (torch.randn((E, H), generator=g) * 0.05).to(torch.bfloat16)
+        _, _, L = oracle64.route(x.float().numpy(), Wr.float().numpy(), None, K, False, want_logits=True)
+        assert np.unique(L).size > T * E // 2
+        expect = np.arange(K, dtype=np.int32)[None, :]
+        for t in range(T):
+            for sign in (1.0, -1.0):
+                bias = torch.from_numpy(-sign * L[t]).contiguous()
+                ids, w = moe.moe_route(x[t:t + 1].cuda(), (Wr * sign).to(torch.bfloat16).cuda(), bias.cuda(), K, False)
+                torch.cuda.synchronize()
+                assert np.array_equal(ids.cpu().numpy(), expect), (t, sign, ids.cpu().numpy())
+                assert np.allclose(w.cpu().numpy(), 1.0 / E, rtol=1e-6)
+                ids_o, _ = oracle64.route(x[t:t + 1].float().numpy(), (Wr * sign).float().numpy(), bias.numpy(), K, False)
+                assert np.array_equal(ids_o, expect)
+
+
 def test_route_slices_equal_the_whole(moe):
     wl = workloads.tenants(seed=3, n_tenants=4, T_per=64, I=64, Is=0).to("cuda")
     ids_all, w_all = moe.moe_route(wl.x, wl.Wr, wl.bias[1], 4, False)

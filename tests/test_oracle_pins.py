@@ -38,39 +38,46 @@ def test_router_dot_exact_on_integers(oracle64):
 
 
 def test_router_dot_order_hand_worked(oracle64):
-    # Hand-worked case where the summation order changes the fp32 result.
-    # Products (w = 1): x[0] = 2^24, x[8] = 1, x[9] = 1, x[16] = -2^24, everything else 0.
-    # Fixed order: element h goes to partial (h/8) mod 64, so partial0 = 2^24, partial1 = 1+1 = 2,
-    # partial2 = -2^24.  Butterfly: stages 32,16,8,4 add zeros; stage 2 gives a0 = 2^24 - 2^24 = 0
-    # and a1 = 2 + 0 = 2; stage 1 gives 0 + 2 = 2.
-    # (A single left-to-right sum would give 2^24 + 1 -> 2^24, + 1 -> 2^24, - 2^24 = 0.)
+    # Hand-worked cases where the summation order changes the fp32 result (w = 1 everywhere, so the
+    # products are the x values).  Element h goes to partial (h/8) mod 64; the partials are folded
+    # by a[j] += a[j xor s] for s = 1, 2, 4, ...
     H = 64
-    x = np.zeros((1, H), np.float32)
-    x[0, 0], x[0, 8], x[0, 9], x[0, 16] = 2.0 ** 24, 1.0, 1.0, -(2.0 ** 24)
     Wr = np.ones((1, H), np.float32)
-    _, _, logits = oracle64.route(x, Wr, None, K=1, renorm=False, want_logits=True)
-    assert logits[0, 0] == 2.0
 
-    # Same lane, sequential: x[0] = 2^24, x[1] = 1, x[2] = 1 all fall in partial 0:
+    def logit(values):
+        x = np.zeros((1, H), np.float32)
+        for h, v in values.items():
+            x[0, h] = v
+        return oracle64.route(x, Wr, None, K=1, renorm=False, want_logits=True)[2][0, 0]
+
+    B = 2.0 ** 24
+    # partials p0 = 2^24 (h=0), p1 = 1 (h=8), p2 = -2^24 (h=16), p3 = 1 (h=24).
+    # stride 1: p0+p1 = 2^24+1 -> rounds to 2^24 (tie to even); p2+p3 = -2^24+1 = -16777215 (exact).
+    # stride 2: 2^24 - 16777215 = 1.   Strides 4..32 add zeros.
+    # (Folding stride 2 first would give (p0+p2) + (p1+p3) = 0 + 2 = 2; one left-to-right sum gives
+    #  2^24+1 -> 2^24, -2^24 -> 0, +1 -> 1 as well, which the next case separates.)
+    assert logit({0: B, 8: 1.0, 16: -B, 24: 1.0}) == 1.0
+    # partials p0 = 2^24, p1 = -2^24, p2 = 1, p3 = 1: stride 1: 0 and 2; stride 2: 2.
+    # and p0 = 2^24, p1 = 1, p2 = 1, p3 = -2^24: stride 1: 2^24 and -16777215; stride 2: 1
+    # (a left-to-right sum gives 2^24+1 -> 2^24, +1 -> 2^24, -2^24 -> 0).
+    assert logit({0: B, 8: -B, 16: 1.0, 24: 1.0}) == 2.0
+    assert logit({0: B, 8: 1.0, 16: 1.0, 24: -B}) == 1.0
+
+    # Same partial, sequential: x[0] = 2^24, x[1] = 1, x[2] = 1 all fall in partial 0:
     # 2^24 + 1 rounds back to 2^24 twice; a pairwise order would give 2^24 + 2.
-    x = np.zeros((1, H), np.float32)
-    x[0, 0], x[0, 1], x[0, 2] = 2.0 ** 24, 1.0, 1.0
-    _, _, logits = oracle64.route(x, Wr, None, K=1, renorm=False, want_logits=True)
-    assert logits[0, 0] == 2.0 ** 24
+    assert logit({0: B, 1: 1.0, 2: 1.0}) == B
 
-    # Wrap-around: with H = 1024, h = 0 and h = 512 share partial 0 ((512/8) mod 64 = 0) and are
-    # taken in ascending h: (2^24 + 1) -> 2^24, then h = 513: + 1 -> 2^24 again.
+    # Wrap-around and the widest stride, H = 1024: h = 0 and h = 512 share partial 0
+    # ((512/8) mod 64 = 0) and are taken in ascending h: 2^24 + 1 -> 2^24, then h = 513: again 2^24.
     H = 1024
-    x = np.zeros((1, H), np.float32)
-    x[0, 0], x[0, 512], x[0, 513] = 2.0 ** 24, 1.0, 1.0
     Wr = np.ones((1, H), np.float32)
-    _, _, logits = oracle64.route(x, Wr, None, K=1, renorm=False, want_logits=True)
-    assert logits[0, 0] == 2.0 ** 24
+    assert logit({0: B, 512: 1.0, 513: 1.0}) == B
     # ... while h = 8 and h = 9 sit in partial 1 and survive: 2^24 + (1 + 1).
-    x = np.zeros((1, H), np.float32)
-    x[0, 0], x[0, 8], x[0, 9] = 2.0 ** 24, 1.0, 1.0
-    _, _, logits = oracle64.route(x, Wr, None, K=1, renorm=False, want_logits=True)
-    assert logits[0, 0] == 2.0 ** 24 + 2.0
+    assert logit({0: B, 8: 1.0, 9: 1.0}) == B + 2.0
+    # partials p0 = 2^24 (h=0), p32 = 1 (h=256), p33 = 1 (h=264), p1 = -2^24 (h=8):
+    # stride 1: (p0+p1) = 0 in partials 0,1; (p32+p33) = 2 in partials 32,33; stride 32: 0 + 2 = 2.
+    # With the widest stride first: (p0+p32) = 2^24+1 -> 2^24, (p1+p33) = -2^24+1 = -16777215, sum 1.
+    assert logit({0: B, 256: 1.0, 264: 1.0, 8: -B}) == 2.0
 
 
 def test_router_dot_fused_multiply_add(oracle64):
@@ -108,7 +115,7 @@ def test_router_dot_order_in_numpy(oracle64):
             ok = cols < H
             prod = x[:, None, cols[ok]] * Wr[None, :, cols[ok]]
             a[:, :, ok] = a[:, :, ok] + prod
-    for s in (32, 16, 8, 4, 2, 1):
+    for s in (1, 2, 4, 8, 16, 32):
         a = a + a[:, :, np.arange(64) ^ s]
     _, _, logits = oracle64.route(x, Wr, None, K=4, renorm=False, want_logits=True)
     assert np.array_equal(logits, a[:, :, 0])
