@@ -16,46 +16,71 @@
 // b mod 8; the index walk hands each XCD runs of consecutive tiles that share weight and token
 // panels, so they meet in that XCD's L2.
 //
-// Inside a tile: 4 waves, K steps of 64 through a double-buffered LDS stage (16-byte chunks,
-// chunk index xor row&7 so the MFMA operand reads are bank-conflict free), global loads of step
-// k+1 are in flight while step k is multiplied.  MFMA 32x32x16 bf16 with the WEIGHT rows as the
+// Inside a tile: 4 waves, K steps of 32 through a ring of NS LDS stages.  Both panels are copied
+// from global memory straight into LDS (global_load_lds, 16 bytes per lane, no registers in
+// between); NS-1 stages are in flight while one is multiplied, which hides the memory latency a
+// single prefetched stage cannot.  The copies are asynchronous: a wave waits with
+// s_waitcnt vmcnt(n) until only the copies of later stages are outstanding, then one workgroup
+// barrier per K step publishes the stage.  Operand fragments are double-buffered in registers so
+// every LDS read is issued one MFMA group ahead of its use.  Staged rows are 64 bytes (4 chunks of 16); a row's
+// chunks are stored at slot = chunk xor (row/2)%4 so the MFMA operand reads (32 rows, same chunk)
+// are bank-conflict free.  MFMA 32x32x16 bf16 with the WEIGHT rows as the
 // first operand and the TOKEN rows as the second: a lane then owns 4 consecutive output columns
 // of one token row per accumulator quad, which makes the bf16 stores 8 bytes wide.
-// Rows past the end of an expert are clamped on load and masked on store; 32-row token blocks
-// that are entirely past the end are skipped.
+// Rows past the end of an expert are clamped on load (they recompute the expert's last row) and
+// masked on store, which keeps the K loop free of branches.
 #include "common.h"
 
 namespace moe {
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, bool GATEUP>
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool GATEUP, int NS>
 struct TileShape {
-  static constexpr int BK = 64;
-  static constexpr int ROWB = BK * 2;             // bytes per staged row
+  static constexpr int BK = 32;
+  static constexpr int ROWB = BK * 2;             // bytes per staged row (4 chunks of 16 bytes)
   static constexpr int WTM = BM / WAVES_M;        // token rows per wave
   static constexpr int WTN = BN / WAVES_N;        // weight rows per wave
   static constexpr int TB = WTM / 32;             // 32-row token blocks per wave
   static constexpr int NB = WTN / 32;             // 32-row weight blocks per wave
   static constexpr int NBH = GATEUP ? NB / 2 : NB;
-  static constexpr int LA = BM / 32;              // 16-byte global loads per thread and K step (tokens)
-  static constexpr int LB = BN / 32;              // (weights)
   static constexpr int STAGE = (BM + BN) * ROWB;  // bytes per LDS stage
+  static constexpr int NL = (BM + BN) / 64;       // 1 KB (16-row) copies per wave and stage
+  static constexpr int NLA = BM / 64;             // the first NLA of them are token rows
+  static constexpr int NF = TB + NB;              // operand fragments per wave and 16-wide K slice
+  static constexpr int NM = TB * NB;              // MFMAs per wave and 16-wide K slice
+  static constexpr int DIST = NS - 1;             // stages in flight while one is being multiplied
   static constexpr int NOUT = GATEUP ? BN / 2 : BN;  // output columns per tile
   static_assert(WAVES_M * WAVES_N == 4, "four waves per workgroup");
   static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile is made of 32x32 blocks");
   static_assert(!GATEUP || NB % 2 == 0, "gate and up blocks come in pairs");
+  static_assert(BM % 64 == 0 && BN % 128 == 0, "copies of 16 rows are dealt to 4 waves");
 };
 
 constexpr int TILE_EMAX = 256;
 constexpr int TILE_GM = 4;   // token tiles per locality group
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, bool GATEUP>
+// One 16-byte-per-lane copy from global memory straight into LDS (no registers in between):
+// lane l of the wave writes LDS bytes [lds + 16*l, +16) from global address base + voff.
+// The copy is asynchronous; it is counted by vmcnt like any other vector memory load.
+__device__ __forceinline__ void copy_to_lds_16(const void* base, uint32_t voff, uint32_t lds) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(base), "s"(lds)
+               : "memory", "m0");
+}
+template <int N>
+__device__ __forceinline__ void wait_copies_but() {   // all but the N most recent copies have landed
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+__device__ __forceinline__ void workgroup_barrier() { asm volatile("s_barrier" ::: "memory"); }
+__device__ __forceinline__ void wait_lds_reads() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool GATEUP, int NS>
 __global__ __launch_bounds__(256, 1) void expert_tile_kernel(GemmArgs a) {
-  using S = TileShape<BM, BN, WAVES_M, WAVES_N, GATEUP>;
+  using S = TileShape<BM, BN, WAVES_M, WAVES_N, GATEUP, NS>;
   extern __shared__ __align__(16) unsigned char smem[];
   __shared__ int s_pref[TILE_EMAX + 1];
   __shared__ int s_rb[TILE_EMAX + 1];
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave / WAVES_N, wn = wave % WAVES_N;
   const int nexp = a.offsets ? a.hi - a.lo : 1;
 
@@ -93,11 +118,16 @@ __global__ __launch_bounds__(256, 1) void expert_tile_kernel(GemmArgs a) {
   const int groupTiles = TILE_GM * NT;
   const int Lend = ((totalM + TILE_GM - 1) / TILE_GM) * groupTiles;
 
-  // staging assignment of this thread: chunk lchk of rows lrow + 32*i
-  const int lrow = tid >> 3, lchk = tid & 7;
-  const int lds_w = lrow * S::ROWB + ((lchk ^ (lrow & 7)) << 4);
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
+  // copy assignment of this lane inside a 16-row block: row lane/4, 16-byte slot lane%4; the slot
+  // holds chunk (slot xor swz) of the row, swz = (row/2)%4, which spreads the MFMA operand reads
+  // (32 rows at the same chunk) over all banks.
+  const int crow = lane >> 2;
+  const int cchunk = (lane & 3) ^ ((lane >> 3) & 3);
+  // operand reads: row lane%32 of a 32-row block, chunk 2*kk + lane/32
   const int frag_row = lane & 31;
   const int frag_half = lane >> 5;
+  const int frag_swz = (lane >> 1) & 3;
 
   const int G = gridDim.x;
   const bool xcd_walk = (G % 8) == 0;
@@ -123,20 +153,24 @@ __global__ __launch_bounds__(256, 1) void expert_tile_kernel(GemmArgs a) {
     const int n0 = nt * S::NOUT;
     const int eg = a.offsets ? a.lo + e : 0;
 
-    const bf16_t* Ag = a.A + (size_t)row0 * Kdim;
-    const bf16_t* Bg0 = a.B0 + (size_t)eg * a.N * Kdim;
-    const bf16_t* Bg1 = GATEUP ? a.B1 + (size_t)eg * a.N * Kdim : nullptr;
-    int offA[S::LA], offB[S::LB];
+    const unsigned char* Ag = reinterpret_cast<const unsigned char*>(a.A + (size_t)row0 * Kdim);
+    const unsigned char* Bg0 = reinterpret_cast<const unsigned char*>(a.B0 + (size_t)eg * a.N * Kdim);
+    const unsigned char* Bg1 = GATEUP ? reinterpret_cast<const unsigned char*>(a.B1 + (size_t)eg * a.N * Kdim) : nullptr;
+    // byte offsets of this lane's 16 bytes for each of the NL copies of a stage (K step 0)
+    uint32_t coff[S::NL];
 #pragma unroll
-    for (int i = 0; i < S::LA; ++i) offA[i] = min(lrow + 32 * i, rowsValid - 1) * Kdim + lchk * 8;
-#pragma unroll
-    for (int i = 0; i < S::LB; ++i) {
-      int r = lrow + 32 * i;
-      if (GATEUP && i >= S::LB / 2) r -= BN / 2;   // second half of the staged rows: the up branch
-      offB[i] = min(n0 + r, a.N - 1) * Kdim + lchk * 8;
+    for (int i = 0; i < S::NL; ++i) {
+      const int row = (i * 4 + wave) * 16 + crow;       // row inside the stage: tokens first, then weights
+      int grow;
+      if (i < S::NLA) {
+        grow = min(row, rowsValid - 1);
+      } else {
+        int r = row - BM;
+        if (GATEUP && i >= S::NLA + (S::NL - S::NLA) / 2) r -= BN / 2;   // second half: the up branch
+        grow = min(n0 + r, a.N - 1);
+      }
+      coff[i] = (uint32_t)grow * (uint32_t)Kdim * 2u + (uint32_t)cchunk * 16u;
     }
-    // 32-row token blocks of this wave that hold at least one valid row
-    const int tbValid = min(S::TB, (rowsValid - wm * S::WTM + 31) / 32);
 
     f32x16 acc[S::NB][S::TB];
 #pragma unroll
@@ -146,69 +180,107 @@ __global__ __launch_bounds__(256, 1) void expert_tile_kernel(GemmArgs a) {
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[nb][tb][i] = 0.0f;
 
-    u32x4 ra[S::LA], rb[S::LB];
-    // global -> registers for K step k0 (both panels), and registers -> LDS stage
-#define MOE_TILE_GLOAD(k0)                                                                      \
-    {                                                                                           \
-      _Pragma("unroll") for (int i = 0; i < S::LA; ++i)                                         \
-        ra[i] = *reinterpret_cast<const u32x4*>(Ag + offA[i] + (k0));                           \
-      _Pragma("unroll") for (int i = 0; i < S::LB; ++i)                                         \
-        rb[i] = *reinterpret_cast<const u32x4*>(((GATEUP && i >= S::LB / 2) ? Bg1 : Bg0) + offB[i] + (k0)); \
-    }
-#define MOE_TILE_LSTORE(stage)                                                                  \
-    {                                                                                           \
-      unsigned char* As_ = smem + (stage) * S::STAGE;                                           \
-      unsigned char* Bs_ = As_ + BM * S::ROWB;                                                  \
-      _Pragma("unroll") for (int i = 0; i < S::LA; ++i)                                         \
-        *reinterpret_cast<u32x4*>(As_ + lds_w + i * 32 * S::ROWB) = ra[i];                      \
-      _Pragma("unroll") for (int i = 0; i < S::LB; ++i)                                         \
-        *reinterpret_cast<u32x4*>(Bs_ + lds_w + i * 32 * S::ROWB) = rb[i];                      \
-    }
+    // copy i (of NL) of K step kt into stage buffer st; all NL of them
+#define MOE_TILE_ISSUE1(kt, st, i)                                                                  \
+    copy_to_lds_16(((i) < S::NLA ? Ag : ((GATEUP && (i) >= S::NLA + (S::NL - S::NLA) / 2) ? Bg1 : Bg0)) + (size_t)(kt) * S::ROWB, \
+                   coff[i], lds0 + (uint32_t)(st) * S::STAGE + (uint32_t)wave * 1024u + (uint32_t)(i) * 4096u);
+#define MOE_TILE_ISSUE(kt, st)                                                                      \
+    { _Pragma("unroll") for (int i = 0; i < S::NL; ++i) MOE_TILE_ISSUE1(kt, st, i); }
 
-    MOE_TILE_GLOAD(0);
-    MOE_TILE_LSTORE(0);
-    __syncthreads();
-    for (int kt = 0; kt < nk; ++kt) {
-      const int cur = kt & 1;
-      const bool more = kt + 1 < nk;
-      if (more) MOE_TILE_GLOAD((kt + 1) * S::BK);
-      const unsigned char* As = smem + cur * S::STAGE;
-      const unsigned char* Bs = As + BM * S::ROWB;
-#pragma unroll
-      for (int kk = 0; kk < 4; ++kk) {
-        const int coff = ((kk * 2 + frag_half) ^ (lane & 7)) << 4;
-        bf16x8 fa[S::TB], fb[S::NB];
-#pragma unroll
-        for (int tb = 0; tb < S::TB; ++tb)
-          fa[tb] = as_bf16x8(*reinterpret_cast<const u32x4*>(As + (wm * S::WTM + tb * 32 + frag_row) * S::ROWB + coff));
-#pragma unroll
-        for (int nb = 0; nb < S::NB; ++nb) {
-          const int brow = GATEUP ? ((nb < S::NBH ? 0 : BN / 2) + wn * (S::WTN / 2) + (nb % S::NBH) * 32)
-                                  : (wn * S::WTN + nb * 32);
-          fb[nb] = as_bf16x8(*reinterpret_cast<const u32x4*>(Bs + (brow + frag_row) * S::ROWB + coff));
-        }
-#pragma unroll
-        for (int tb = 0; tb < S::TB; ++tb) {
-          if (tb < tbValid) {
-#pragma unroll
-            for (int nb = 0; nb < S::NB; ++nb)
-              acc[nb][tb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fb[nb], fa[tb], acc[nb][tb], 0, 0, 0);
-          }
-        }
-      }
-      if (more) MOE_TILE_LSTORE(cur ^ 1);
-      __syncthreads();
+    // fragment f of the 16-wide K slice kk_ of a stage, LDS -> registers: f < TB is the token block
+    // f, otherwise the weight block f - TB
+#define MOE_TILE_READ1(fa_, fb_, stage_, kk_, f_)                                                   \
+    {                                                                                               \
+      const unsigned char* As_ = smem + (stage_) * S::STAGE;                                         \
+      const int cr_ = (((kk_) * 2 + frag_half) ^ frag_swz) << 4;                                     \
+      if ((f_) < S::TB) {                                                                           \
+        fa_[(f_) < S::TB ? (f_) : 0] = as_bf16x8(*reinterpret_cast<const u32x4*>(                    \
+            As_ + (wm * S::WTM + (f_) * 32 + frag_row) * S::ROWB + cr_));                            \
+      } else {                                                                                      \
+        const int nb_ = (f_) < S::TB ? 0 : (f_) - S::TB;                                            \
+        const int brow_ = GATEUP ? ((nb_ < S::NBH ? 0 : BN / 2) + wn * (S::WTN / 2) + (nb_ % S::NBH) * 32) \
+                                 : (wn * S::WTN + nb_ * 32);                                         \
+        fb_[nb_] = as_bf16x8(*reinterpret_cast<const u32x4*>(                                        \
+            As_ + BM * S::ROWB + (brow_ + frag_row) * S::ROWB + cr_));                               \
+      }                                                                                             \
     }
-#undef MOE_TILE_GLOAD
-#undef MOE_TILE_LSTORE
+#define MOE_TILE_READ(fa_, fb_, stage_, kk_)                                                        \
+    { _Pragma("unroll") for (int f = 0; f < S::NF; ++f) MOE_TILE_READ1(fa_, fb_, stage_, kk_, f); }
+#define MOE_TILE_MFMA1(fa_, fb_, j_)                                                                \
+    acc[(j_) % S::NB][(j_) / S::NB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                       \
+        fb_[(j_) % S::NB], fa_[(j_) / S::NB], acc[(j_) % S::NB][(j_) / S::NB], 0, 0, 0);
+#define MOE_TILE_MMA(fa_, fb_)                                                                      \
+    { _Pragma("unroll") for (int j = 0; j < S::NM; ++j) MOE_TILE_MFMA1(fa_, fb_, j); }
+    // First half of a stage: multiply slice 0 (set A) and, spread between the MFMAs, read the
+    // fragments of slice 1 into set B.  The scheduling fences pin that interleaving, so no LDS read
+    // is issued in front of an idle matrix pipe.
+#define MOE_TILE_HALF1(stage_)                                                                      \
+    { _Pragma("unroll") for (int j = 0; j < S::NM; ++j) {                                           \
+        MOE_TILE_MFMA1(faA, fbA, j);                                                                \
+        _Pragma("unroll") for (int f = 0; f < S::NF; ++f)                                           \
+          if (f * S::NM / S::NF == j) MOE_TILE_READ1(faB, fbB, stage_, 1, f);                        \
+        __builtin_amdgcn_sched_barrier(0x6);                                                        \
+    } __builtin_amdgcn_sched_barrier(0); }
+    // Second half: multiply slice 1 (set B); between the MFMAs first request the copies of the
+    // stage that reuses the buffer just freed (ISSUE_), then read slice 0 of the next stage into set A.
+#define MOE_TILE_HALF2(next_stage_, kt_issue_, st_issue_)                                                    \
+    { _Pragma("unroll") for (int j = 0; j < S::NM; ++j) {                                           \
+        MOE_TILE_MFMA1(faB, fbB, j);                                                                \
+        _Pragma("unroll") for (int q = 0; q < S::NL + S::NF; ++q)                                   \
+          if (q * S::NM / (S::NL + S::NF) == j) {                                                   \
+            if (q < S::NL) { MOE_TILE_ISSUE1(kt_issue_, st_issue_, q < S::NL ? q : 0); }             \
+            else MOE_TILE_READ1(faA, fbA, next_stage_, 0, q < S::NL ? 0 : q - S::NL);               \
+          }                                                                                         \
+        __builtin_amdgcn_sched_barrier(0x6);                                                        \
+    } }
+
+    // Pipeline.  All NS stages are requested up front; while stage kt is multiplied, stages
+    // kt+1 .. kt+NS-1 are in flight.  The fragments of the second K slice of a stage are read
+    // while the first slice is multiplied, and the first slice of the NEXT stage is read (after
+    // the barrier that publishes it) while the second slice is multiplied, so neither LDS read
+    // waits in front of an idle matrix pipe.  The barrier between the two slices also tells every
+    // wave that stage kt has been read completely, so its buffer can take the copy of stage kt+NS.
+    // (Past the end of K the requests repeat the last K step into a buffer nobody reads again:
+    // every iteration then issues the same number of copies and the wait counts stay constant.)
+#pragma unroll
+    for (int s = 0; s < NS; ++s) MOE_TILE_ISSUE(min(s, nk - 1), s);
+    wait_copies_but<S::DIST * S::NL>();
+    workgroup_barrier();
+    bf16x8 faA[S::TB], fbA[S::NB], faB[S::TB], fbB[S::NB];
+    MOE_TILE_READ(faA, fbA, 0, 0);
+    for (int kt = 0; kt + 1 < nk; ++kt) {
+      MOE_TILE_HALF1(kt % NS);
+      // this wave has finished reading stage kt once the second-slice fragments are in registers
+      // (the empty asm makes the compiler wait for them)
+#pragma unroll
+      for (int tb = 0; tb < S::TB; ++tb) asm volatile("" : "+v"(faB[tb]));
+#pragma unroll
+      for (int nb = 0; nb < S::NB; ++nb) asm volatile("" : "+v"(fbB[nb]));
+      wait_copies_but<(S::DIST - 1) * S::NL>();
+      workgroup_barrier();  // stage kt+1 is complete for everyone; stage kt is free for everyone
+      MOE_TILE_HALF2((kt + 1) % NS, min(kt + NS, nk - 1), kt % NS);
+    }
+    MOE_TILE_READ(faB, fbB, (nk - 1) % NS, 1);
+    MOE_TILE_MMA(faA, fbA);
+    MOE_TILE_MMA(faB, fbB);
+    wait_lds_reads();
+    workgroup_barrier();   // the next tile's first copies overwrite stages other waves may still read
+#undef MOE_TILE_READ1
+#undef MOE_TILE_MFMA1
+#undef MOE_TILE_HALF1
+#undef MOE_TILE_HALF2
+#undef MOE_TILE_ISSUE1
+#undef MOE_TILE_READ
+#undef MOE_TILE_MMA
+#undef MOE_TILE_ISSUE
 
     // epilogue: accumulator element i of block (nb, tb) is output column
     // 8*(i/4) + 4*(lane/32) + i%4 of the block, token row lane%32.
 #pragma unroll
     for (int tb = 0; tb < S::TB; ++tb) {
       const int m = row0 + wm * S::WTM + tb * 32 + frag_row;
-      if (tb < tbValid && m < rowEnd) {
-        bf16_t* crow = a.C + (size_t)m * a.N;
+      if (m < rowEnd) {
+        bf16_t* crow_out = a.C + (size_t)m * a.N;
 #pragma unroll
         for (int nb = 0; nb < S::NBH; ++nb) {
           const int nbase = n0 + (GATEUP ? wn * (S::WTN / 2) : wn * S::WTN) + nb * 32 + 4 * frag_half;
@@ -230,7 +302,7 @@ __global__ __launch_bounds__(256, 1) void expert_tile_kernel(GemmArgs a) {
               uint2 o;
               o.x = pack_bf16x2(v[0], v[1]);
               o.y = pack_bf16x2(v[2], v[3]);
-              *reinterpret_cast<uint2*>(crow + n) = o;
+              *reinterpret_cast<uint2*>(crow_out + n) = o;
             }
           }
         }
@@ -250,12 +322,12 @@ static int num_cus() {
   return cus;
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, bool GATEUP>
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool GATEUP, int NS>
 static int launch_tile_t(const GemmArgs& a, hipStream_t st) {
-  using S = TileShape<BM, BN, WAVES_M, WAVES_N, GATEUP>;
-  auto kern = expert_tile_kernel<BM, BN, WAVES_M, WAVES_N, GATEUP>;
+  using S = TileShape<BM, BN, WAVES_M, WAVES_N, GATEUP, NS>;
+  auto kern = expert_tile_kernel<BM, BN, WAVES_M, WAVES_N, GATEUP, NS>;
   static bool attr_set = false;
-  const int lds = 2 * S::STAGE;
+  const int lds = NS * S::STAGE;
   if (!attr_set) {
     if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess) return -4;
     attr_set = true;
@@ -271,12 +343,12 @@ static int launch_tile_t(const GemmArgs& a, hipStream_t st) {
 }
 
 int launch_tile_gateup(const GemmArgs& a, int tile_rows, hipStream_t st) {
-  if (tile_rows >= 256) return launch_tile_t<256, 256, 2, 2, true>(a, st);
-  return launch_tile_t<128, 256, 1, 4, true>(a, st);
+  if (tile_rows >= 256) return launch_tile_t<256, 256, 2, 2, true, 4>(a, st);
+  return launch_tile_t<128, 256, 1, 4, true, 4>(a, st);
 }
 int launch_tile_down(const GemmArgs& a, int tile_rows, hipStream_t st) {
-  if (tile_rows >= 256) return launch_tile_t<256, 256, 2, 2, false>(a, st);
-  return launch_tile_t<128, 256, 1, 4, false>(a, st);
+  if (tile_rows >= 256) return launch_tile_t<256, 256, 2, 2, false, 4>(a, st);
+  return launch_tile_t<128, 256, 1, 4, false, 4>(a, st);
 }
 
 }  // namespace moe
