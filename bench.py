@@ -86,7 +86,8 @@ def main() -> int:
 
     def step(events=None):
         route()
-        moe.moe_permute(buf.topk_ids, g.x, s.E, buf.expert_offsets, buf.src_of_row, buf.row_of_pair, buf.Xp)
+        moe.moe_permute(buf.topk_ids, g.x, s.E, buf.expert_offsets, buf.src_of_row, buf.row_of_pair, buf.Xp,
+                        buf.workspace_permute)
         if events is None:
             for lo, hi in groups:
                 moe.moe_expert_group_forward(lo, hi, buf.Xp, buf.expert_offsets, g.Wg, g.Wu, g.Wd, buf.Yp,

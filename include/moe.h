@@ -75,7 +75,8 @@ int moe_route(const void* x, const void* Wr, const float* bias, int T, int H, in
  * expert_offsets[lo] .. expert_offsets[hi]-1 of Xp.
  *   topk_ids [T,K] int32 with values in [0,E) (values outside are not detected);
  *   x [T,H] bf16; expert_offsets [E+1]; src_of_row [P]; row_of_pair [P]; Xp [P,H] bf16.
- * workspace: not used at present (may be NULL); moe_permute_workspace_bytes returns 0.
+ * workspace: moe_permute_workspace_bytes(T, K, E) bytes of scratch (pairs of each expert per chunk of
+ * 64 pairs); contents are meaningless after the call.
  */
 int moe_permute(const int32_t* topk_ids, const void* x, int T, int H, int E, int K,
                 int32_t* expert_offsets, int32_t* src_of_row, int32_t* row_of_pair, void* Xp,
@@ -132,7 +133,8 @@ int moe_combine(const void* Yp, const int32_t* row_of_pair, const float* topk_w,
  * The same two calls with the kernel shape picked by the caller instead of by the library
  * (measurement and tuning).  policy: 0 = automatic (what the plain calls use); 1 = weight-streaming
  * kernels, one 16-row weight block per wave; 2 = weight-streaming kernels with K split over the 4
- * waves of a workgroup; 3 = MFMA tiles of 128 token rows; 4 = MFMA tiles of 256 token rows.
+ * waves of a workgroup; 3 = MFMA tiles of 128 token rows, two workgroups per CU; 4 = MFMA tiles of
+ * 256 token rows; 5 = MFMA tiles of 128 token rows, one workgroup per CU.
  * Every policy computes the same function; results may differ in the last bf16 bit between
  * policies because the fp32 summation order differs.  Use one policy for all blocks of a layer.
  * Adding 0x100 to policy runs only the first kernel of the call (gate/up projections and SwiGLU

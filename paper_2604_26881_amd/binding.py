@@ -109,7 +109,8 @@ def moe_route(x, Wr, bias, K: int, renorm: bool, topk_ids=None, topk_w=None):
     return topk_ids, topk_w
 
 
-def moe_permute(topk_ids, x, E: int, expert_offsets=None, src_of_row=None, row_of_pair=None, Xp=None):
+def moe_permute(topk_ids, x, E: int, expert_offsets=None, src_of_row=None, row_of_pair=None, Xp=None,
+                workspace=None):
     T, K = topk_ids.shape
     H = x.shape[1]
     dev = x.device
@@ -121,10 +122,14 @@ def moe_permute(topk_ids, x, E: int, expert_offsets=None, src_of_row=None, row_o
         row_of_pair = torch.empty(T * K, dtype=torch.int32, device=dev)
     if Xp is None:
         Xp = torch.empty((T * K, H), dtype=torch.bfloat16, device=dev)
+    if workspace is None:
+        workspace = torch.empty(max(int(load().moe_permute_workspace_bytes(T, K, E)), 256), dtype=torch.uint8,
+                                device=dev)
     rc = load().moe_permute(_ptr(topk_ids, torch.int32, "topk_ids"), _ptr(x, torch.bfloat16, "x"), T, H, E, K,
                             _ptr(expert_offsets, torch.int32, "expert_offsets"),
                             _ptr(src_of_row, torch.int32, "src_of_row"),
-                            _ptr(row_of_pair, torch.int32, "row_of_pair"), _ptr(Xp, torch.bfloat16, "Xp"), None, 0,
+                            _ptr(row_of_pair, torch.int32, "row_of_pair"), _ptr(Xp, torch.bfloat16, "Xp"),
+                            _ptr(workspace, None, "workspace"), workspace.numel() * workspace.element_size(),
                             _stream())
     _check(rc, "moe_permute")
     return expert_offsets, src_of_row, row_of_pair, Xp
@@ -185,6 +190,7 @@ class LayerBuffers:
     out: torch.Tensor
     workspace: torch.Tensor
     workspace_shared: Optional[torch.Tensor]
+    workspace_permute: Optional[torch.Tensor] = None
 
     @staticmethod
     def allocate(T: int, H: int, E: int, K: int, I: int, Is: int, device="cuda") -> "LayerBuffers":
@@ -201,7 +207,9 @@ class LayerBuffers:
             S=torch.empty((T, H), **bf) if Is > 0 else None,
             sg=torch.empty(T, dtype=torch.float32, device=device) if Is > 0 else None,
             out=torch.empty((T, H), **bf), workspace=torch.empty(ws, dtype=torch.uint8, device=device),
-            workspace_shared=torch.empty(max(wss, 256), dtype=torch.uint8, device=device) if Is > 0 else None)
+            workspace_shared=torch.empty(max(wss, 256), dtype=torch.uint8, device=device) if Is > 0 else None,
+            workspace_permute=torch.empty(max(int(lib.moe_permute_workspace_bytes(T, K, E)), 256), dtype=torch.uint8,
+                                          device=device))
 
 
 def moe_layer_forward(x, Wr, bias, Wg, Wu, Wd, shared, K: int, renorm: bool,
@@ -223,7 +231,8 @@ def moe_layer_forward(x, Wr, bias, Wg, Wu, Wd, shared, K: int, renorm: bool,
             moe_route(x[a:b], Wr, None if bias is None else bias[i], K, renorm, buf.topk_ids[a:b], buf.topk_w[a:b])
     else:
         moe_route(x, Wr, bias, K, renorm, buf.topk_ids, buf.topk_w)
-    moe_permute(buf.topk_ids, x, E, buf.expert_offsets, buf.src_of_row, buf.row_of_pair, buf.Xp)
+    moe_permute(buf.topk_ids, x, E, buf.expert_offsets, buf.src_of_row, buf.row_of_pair, buf.Xp,
+                buf.workspace_permute)
     for lo, hi in (groups or [(0, E)]):
         moe_expert_group_forward(lo, hi, buf.Xp, buf.expert_offsets, Wg, Wu, Wd, buf.Yp, buf.workspace, policy)
     if shared is not None:

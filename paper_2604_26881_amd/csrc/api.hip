@@ -14,7 +14,8 @@ bool dims_ok(int H) { return H > 0 && H % 64 == 0; }
 // Which kernels serve an FFN with `mean_rows` expected rows per expert.  The choice uses only
 // layer-wide sizes (never the block bounds), so a row's result does not depend on the block cut.
 // policy: 0 = automatic; 1 = streaming, no K split; 2 = streaming, K split over 4 waves;
-//         3 = MFMA tiles of 128 rows; 4 = MFMA tiles of 256 rows.
+//         3 = MFMA tiles of 128 rows, two workgroups per CU; 4 = MFMA tiles of 256 rows;
+//         5 = MFMA tiles of 128 rows, one workgroup per CU.
 // Bits 8 and 9 of the policy word restrict a call to one of its two kernels (0x100: gate/up
 // only, 0x200: down projection only), so that each can be timed on its own.
 struct Plan { bool stream; int ksplit; int tile_rows; bool do_gateup; bool do_down; };
@@ -29,6 +30,7 @@ Plan make_plan(int mean_rows, int n_experts_layer, int policy_word) {
     case 2: p.stream = true; p.ksplit = 4; return p;
     case 3: p.stream = false; p.tile_rows = 128; return p;
     case 4: p.stream = false; p.tile_rows = 256; return p;
+    case 5: p.stream = false; p.tile_rows = 129; return p;
     default: break;
   }
   const bool few_experts = n_experts_layer < 16;   // e.g. the shared expert: one weight set, all rows
@@ -37,7 +39,7 @@ Plan make_plan(int mean_rows, int n_experts_layer, int policy_word) {
     p.ksplit = few_experts ? 4 : 1;   // few experts: split K over the waves to get enough of them
   } else {
     p.stream = false;
-    p.tile_rows = mean_rows >= 1024 ? 256 : 128;
+    p.tile_rows = 0;   // 256- or 128-row tiles, picked per kernel from the tile count
   }
   return p;
 }
@@ -70,8 +72,9 @@ const char* moe_status_string(int status) {
 }
 
 size_t moe_permute_workspace_bytes(int T, int K, int E) {
-  (void)T; (void)K; (void)E;
-  return 0;
+  if (T <= 0 || K <= 0 || E <= 0) return 0;
+  const size_t chunks = ((size_t)T * (size_t)K + 63) / 64;   // pairs of each expert per 64-pair chunk
+  return align256(chunks * (size_t)E * 4);
 }
 size_t moe_expert_workspace_bytes(int P, int I) {
   if (P <= 0 || I <= 0) return 0;
@@ -101,12 +104,13 @@ int moe_route(const void* x, const void* Wr, const float* bias, int T, int H, in
 int moe_permute(const int32_t* topk_ids, const void* x, int T, int H, int E, int K, int32_t* expert_offsets,
                 int32_t* src_of_row, int32_t* row_of_pair, void* Xp, void* workspace, size_t workspace_bytes,
                 void* stream) {
-  (void)workspace; (void)workspace_bytes;
   if (T < 0 || !dims_ok(H) || E < 1 || E > 256 || K < 1 || K > 16 || K > E) return MOE_ERR_SHAPE;
   if ((long long)T * K * H >= (1ll << 31)) return MOE_ERR_SHAPE;
   if (!expert_offsets) return MOE_ERR_NULL;
-  if (T > 0 && (!topk_ids || !x || !src_of_row || !row_of_pair || !Xp)) return MOE_ERR_NULL;
-  return launch_permute(topk_ids, x, T, H, E, K, expert_offsets, src_of_row, row_of_pair, Xp, (hipStream_t)stream);
+  if (T > 0 && (!topk_ids || !x || !src_of_row || !row_of_pair || !Xp || !workspace)) return MOE_ERR_NULL;
+  if (T > 0 && workspace_bytes < (((size_t)T * K + 63) / 64) * (size_t)E * 4) return MOE_ERR_WORKSPACE;
+  return launch_permute(topk_ids, x, T, H, E, K, expert_offsets, src_of_row, row_of_pair, Xp, workspace,
+                        (hipStream_t)stream);
 }
 
 int moe_expert_group_forward_ex(int group_lo, int group_hi, const void* Xp, const int32_t* expert_offsets,

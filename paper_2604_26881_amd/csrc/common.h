@@ -57,7 +57,7 @@ struct GemmArgs {
 int launch_route(const void* x, const void* Wr, const float* bias, int T, int H, int E, int K, int renorm,
                  int32_t* ids, float* w, hipStream_t st);
 int launch_permute(const int32_t* ids, const void* x, int T, int H, int E, int K, int32_t* offsets,
-                   int32_t* src_of_row, int32_t* row_of_pair, void* Xp, hipStream_t st);
+                   int32_t* src_of_row, int32_t* row_of_pair, void* Xp, void* workspace, hipStream_t st);
 int launch_combine(const void* Yp, const int32_t* row_of_pair, const float* w, const void* S, const float* sg,
                    int T, int H, int K, void* out, hipStream_t st);
 int launch_gate_dot(const void* x, const void* wgate, int T, int H, float* sg, hipStream_t st);

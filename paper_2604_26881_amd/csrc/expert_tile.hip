@@ -62,7 +62,7 @@ constexpr int TILE_GM = 4;   // token tiles per locality group
 // lane l of the wave writes LDS bytes [lds + 16*l, +16) from global address base + voff.
 // The copy is asynchronous; it is counted by vmcnt like any other vector memory load.
 __device__ __forceinline__ void copy_to_lds_16(const void* base, uint32_t voff, uint32_t lds) {
-  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(base), "s"(lds)
+  asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(base), "s"(lds)
                : "memory", "m0");
 }
 template <int N>
@@ -72,8 +72,8 @@ __device__ __forceinline__ void wait_copies_but() {   // all but the N most rece
 __device__ __forceinline__ void workgroup_barrier() { asm volatile("s_barrier" ::: "memory"); }
 __device__ __forceinline__ void wait_lds_reads() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, bool GATEUP, int NS>
-__global__ __launch_bounds__(256, 1) void expert_tile_kernel(GemmArgs a) {
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool GATEUP, int NS, int OCC>
+__global__ __launch_bounds__(256, OCC) void expert_tile_kernel(GemmArgs a) {
   using S = TileShape<BM, BN, WAVES_M, WAVES_N, GATEUP, NS>;
   extern __shared__ __align__(16) unsigned char smem[];
   __shared__ int s_pref[TILE_EMAX + 1];
@@ -129,11 +129,16 @@ __global__ __launch_bounds__(256, 1) void expert_tile_kernel(GemmArgs a) {
   const int frag_half = lane >> 5;
   const int frag_swz = (lane >> 1) & 3;
 
+  // Tile walk.  Workgroup b runs on XCD b % 8.  Each XCD takes runs of `run` consecutive tile
+  // indices (tiles that share panels), one per workgroup slot; with fewer tiles than slots the runs
+  // shrink so that all eight XCDs still get an equal share.
   const int G = gridDim.x;
   const bool xcd_walk = (G % 8) == 0;
+  const int slot = xcd_walk ? (int)(blockIdx.x >> 3) : 0;
+  const int run = xcd_walk ? max(1, min(G >> 3, (Lend + 7) >> 3)) : 1;
+  if (xcd_walk && slot >= run) return;
   for (int it = 0;; ++it) {
-    const int L = xcd_walk ? ((it * 8 + (int)(blockIdx.x & 7)) * (G >> 3) + (int)(blockIdx.x >> 3))
-                           : (it * G + (int)blockIdx.x);
+    const int L = xcd_walk ? ((it * 8 + (int)(blockIdx.x & 7)) * run + slot) : (it * G + (int)blockIdx.x);
     if (L >= Lend) break;
     const int grp = L / groupTiles, rem = L - grp * groupTiles;
     const int mrow = grp * TILE_GM + rem % TILE_GM;
@@ -322,10 +327,11 @@ static int num_cus() {
   return cus;
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, bool GATEUP, int NS>
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool GATEUP, int NS, int OCC>
 static int launch_tile_t(const GemmArgs& a, hipStream_t st) {
   using S = TileShape<BM, BN, WAVES_M, WAVES_N, GATEUP, NS>;
-  auto kern = expert_tile_kernel<BM, BN, WAVES_M, WAVES_N, GATEUP, NS>;
+  auto kern = expert_tile_kernel<BM, BN, WAVES_M, WAVES_N, GATEUP, NS, OCC>;
+  static_assert(OCC * (NS * S::STAGE + 2100) <= 160 * 1024, "LDS of the resident workgroups must fit a CU");
   static bool attr_set = false;
   const int lds = NS * S::STAGE;
   if (!attr_set) {
@@ -336,19 +342,34 @@ static int launch_tile_t(const GemmArgs& a, hipStream_t st) {
   const int NT = (a.N + S::NOUT - 1) / S::NOUT;
   const long mt_bound = (long)a.rows_total / BM + nexp;
   const long bound = ((mt_bound + TILE_GM - 1) / TILE_GM) * TILE_GM * NT;
-  int grid = (int)(bound < (long)num_cus() ? bound : (long)num_cus());
+  // persistent workgroups: as many as fit on the chip at once (two per CU for the smaller tile)
+  const long resident = (long)num_cus() * OCC;
+  int grid = (int)(bound < resident ? bound : resident);
   if (grid <= 0) return 0;
   hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, st, a);
   return hipGetLastError() == hipSuccess ? 0 : -4;
 }
 
+// tile_rows: 256 or 128 token rows per tile (129: 128-row tiles, one workgroup per CU with a deeper
+// ring); 0 = choose from layer-wide sizes only (never from the block bounds).
+static int pick_tile_rows(const GemmArgs& a, int tile_rows, int nout, bool down) {
+  if (tile_rows != 0) return tile_rows;
+  if (a.offsets != nullptr)   // experts of mixed sizes (measured on Zipf-skewed routing)
+    return (down && a.mean_rows >= 128) ? 256 : 129;
+  const long tiles256 = (((long)a.rows_total + 255) / 256) * ((a.N + nout - 1) / nout);
+  return tiles256 >= (long)num_cus() ? 256 : 129;
+}
 int launch_tile_gateup(const GemmArgs& a, int tile_rows, hipStream_t st) {
-  if (tile_rows >= 256) return launch_tile_t<256, 256, 2, 2, true, 4>(a, st);
-  return launch_tile_t<128, 256, 1, 4, true, 4>(a, st);
+  const int t = pick_tile_rows(a, tile_rows, 128, false);
+  if (t >= 256) return launch_tile_t<256, 256, 2, 2, true, 4, 1>(a, st);
+  if (t == 129) return launch_tile_t<128, 256, 1, 4, true, 4, 1>(a, st);
+  return launch_tile_t<128, 256, 1, 4, true, 3, 2>(a, st);
 }
 int launch_tile_down(const GemmArgs& a, int tile_rows, hipStream_t st) {
-  if (tile_rows >= 256) return launch_tile_t<256, 256, 2, 2, false, 4>(a, st);
-  return launch_tile_t<128, 256, 1, 4, false, 4>(a, st);
+  const int t = pick_tile_rows(a, tile_rows, 256, true);
+  if (t >= 256) return launch_tile_t<256, 256, 2, 2, false, 4, 1>(a, st);
+  if (t == 129) return launch_tile_t<128, 256, 1, 4, false, 4, 1>(a, st);
+  return launch_tile_t<128, 256, 1, 4, false, 3, 2>(a, st);
 }
 
 }  // namespace moe

@@ -49,10 +49,10 @@ __device__ __forceinline__ void widen8(u32x4 v, float* f) {
   f[4] = bf16_lo(v.z); f[5] = bf16_hi(v.z); f[6] = bf16_lo(v.w); f[7] = bf16_hi(v.w);
 }
 
-template <int C, int TOK, int EB>
-__global__ __launch_bounds__(256) void route_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ Wr,
-                                                    const float* __restrict__ bias, int T, int H, int E, int K,
-                                                    int renorm, int32_t* __restrict__ ids, float* __restrict__ w) {
+template <int C, int TOK, int EB, int NW>
+__global__ __launch_bounds__(NW * 64) void route_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ Wr,
+                                                        const float* __restrict__ bias, int T, int H, int E, int K,
+                                                        int renorm, int32_t* __restrict__ ids, float* __restrict__ w) {
   __shared__ float s_logit[TOK][ROUTE_EMAX];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int t0 = blockIdx.x * TOK;
@@ -70,8 +70,8 @@ __global__ __launch_bounds__(256) void route_kernel(const bf16_t* __restrict__ x
     }
   }
 
-  for (int e0 = wave * EB; e0 < E; e0 += 4 * EB) {
-    u32x4 wr[EB][C];
+  // router rows EB at a time; the next batch is requested before the current one is multiplied
+  auto load_batch = [&](u32x4 (&wr)[EB][C], int e0) {
 #pragma unroll
     for (int i = 0; i < EB; ++i) {
       const int e = min(e0 + i, E - 1);
@@ -82,6 +82,8 @@ __global__ __launch_bounds__(256) void route_kernel(const bf16_t* __restrict__ x
         if (h < H) wr[i][c] = *reinterpret_cast<const u32x4*>(Wr + (size_t)e * H + h);
       }
     }
+  };
+  auto dot_batch = [&](const u32x4 (&wr)[EB][C], int e0) {
     float a[EB][TOK];
 #pragma unroll
     for (int i = 0; i < EB; ++i)
@@ -112,10 +114,26 @@ __global__ __launch_bounds__(256) void route_kernel(const bf16_t* __restrict__ x
         }
       }
     }
+  };
+  {
+    constexpr int STEP = NW * EB;
+    u32x4 wrA[EB][C], wrB[EB][C];
+    int e0 = wave * EB;
+    if (e0 < E) load_batch(wrA, e0);
+    while (e0 < E) {
+      const int e1 = e0 + STEP, e2 = e0 + 2 * STEP;
+      if (e1 < E) load_batch(wrB, e1);
+      dot_batch(wrA, e0);
+      if (e1 < E) {
+        if (e2 < E) load_batch(wrA, e2);
+        dot_batch(wrB, e1);
+      }
+      e0 = e2;
+    }
   }
   __syncthreads();
 
-  for (int tk = wave; tk < TOK; tk += 4) {
+  for (int tk = wave; tk < TOK; tk += NW) {
     const int t = t0 + tk;
     if (t >= T) break;
     float l[4];
@@ -163,29 +181,29 @@ __global__ __launch_bounds__(256) void route_kernel(const bf16_t* __restrict__ x
   }
 }
 
-template <int C, int TOK, int EB>
+template <int C, int TOK, int EB, int NW>
 static int launch_route_t(const void* x, const void* Wr, const float* bias, int T, int H, int E, int K, int renorm,
                           int32_t* ids, float* w, hipStream_t st) {
   const int blocks = (T + TOK - 1) / TOK;
-  hipLaunchKernelGGL((route_kernel<C, TOK, EB>), dim3(blocks), dim3(256), 0, st, (const bf16_t*)x,
+  hipLaunchKernelGGL((route_kernel<C, TOK, EB, NW>), dim3(blocks), dim3(NW * 64), 0, st, (const bf16_t*)x,
                      (const bf16_t*)Wr, bias, T, H, E, K, renorm, ids, w);
   return hipGetLastError() == hipSuccess ? 0 : -4;
 }
 
+// Few tokens: one token per workgroup of 8 waves, each wave takes its experts in one batch (latency).
+// Many tokens: two tokens per workgroup of 4 waves, batches of 4 experts (throughput).
+#define MOE_ROUTE_ARGS x, Wr, bias, T, H, E, K, renorm, ids, w, st
 int launch_route(const void* x, const void* Wr, const float* bias, int T, int H, int E, int K, int renorm,
                  int32_t* ids, float* w, hipStream_t st) {
   const int chunks = (H + 511) / 512;
-  const bool many = T >= 2048;  // enough tokens to fill the chip with 4 per workgroup
-  if (chunks <= 1) return many ? launch_route_t<1, 4, 2>(x, Wr, bias, T, H, E, K, renorm, ids, w, st)
-                               : launch_route_t<1, 1, 4>(x, Wr, bias, T, H, E, K, renorm, ids, w, st);
-  if (chunks <= 2) return many ? launch_route_t<2, 4, 2>(x, Wr, bias, T, H, E, K, renorm, ids, w, st)
-                               : launch_route_t<2, 1, 4>(x, Wr, bias, T, H, E, K, renorm, ids, w, st);
-  if (chunks <= 4) return many ? launch_route_t<4, 4, 2>(x, Wr, bias, T, H, E, K, renorm, ids, w, st)
-                               : launch_route_t<4, 1, 4>(x, Wr, bias, T, H, E, K, renorm, ids, w, st);
-  if (chunks <= 8) return many ? launch_route_t<8, 2, 2>(x, Wr, bias, T, H, E, K, renorm, ids, w, st)
-                               : launch_route_t<8, 1, 2>(x, Wr, bias, T, H, E, K, renorm, ids, w, st);
-  if (chunks <= 16) return launch_route_t<16, 1, 1>(x, Wr, bias, T, H, E, K, renorm, ids, w, st);
+  const bool many = T >= 1024;
+  if (chunks <= 1) return many ? launch_route_t<1, 4, 4, 4>(MOE_ROUTE_ARGS) : launch_route_t<1, 1, 8, 8>(MOE_ROUTE_ARGS);
+  if (chunks <= 2) return many ? launch_route_t<2, 2, 4, 4>(MOE_ROUTE_ARGS) : launch_route_t<2, 1, 8, 8>(MOE_ROUTE_ARGS);
+  if (chunks <= 4) return many ? launch_route_t<4, 2, 4, 4>(MOE_ROUTE_ARGS) : launch_route_t<4, 1, 4, 8>(MOE_ROUTE_ARGS);
+  if (chunks <= 8) return many ? launch_route_t<8, 2, 2, 4>(MOE_ROUTE_ARGS) : launch_route_t<8, 1, 2, 8>(MOE_ROUTE_ARGS);
+  if (chunks <= 16) return launch_route_t<16, 1, 1, 4>(MOE_ROUTE_ARGS);
   return -2;
 }
+#undef MOE_ROUTE_ARGS
 
 }  // namespace moe

@@ -42,6 +42,7 @@ def test_workspace_sizes(lib):
     assert lib.moe_shared_workspace_bytes(T, Is) == T * Is * 2
     assert lib.moe_expert_workspace_bytes(3, 64) % 256 == 0 and lib.moe_expert_workspace_bytes(3, 64) >= 3 * 64 * 2
     assert lib.moe_workspace_bytes(T, 2048, 60, 4, I, Is) == max(P * I * 2, T * Is * 2)
+    assert lib.moe_permute_workspace_bytes(T, 4, 60) == (P // 64) * 60 * 4
     assert lib.moe_expert_workspace_bytes(0, 64) == 0
 
 
@@ -56,7 +57,9 @@ def test_bad_arguments_are_rejected_before_any_launch(lib):
     assert lib.moe_route(None, p, None, 4, 64, 8, 2, 0, p, p, None) == NULL
     assert lib.moe_route(None, None, None, 0, 64, 8, 2, 0, None, None, None) == 0   # T = 0: no-op
     # permute
-    assert lib.moe_permute(p, p, 4, 64, 8, 2, None, p, p, p, None, 0, None) == NULL
+    assert lib.moe_permute(p, p, 4, 64, 8, 2, None, p, p, p, p, 1 << 20, None) == NULL
+    assert lib.moe_permute(p, p, 4, 64, 8, 2, p, p, p, p, p, 8, None) == WS
+    assert lib.moe_permute(p, p, 4, 64, 8, 2, p, p, p, p, None, 0, None) == NULL
     assert lib.moe_permute(p, p, 4, 60, 8, 2, p, p, p, p, None, 0, None) == SHAPE
     # expert block: range checks
     args = (p, p, p, p, p, 32, 64, 8, 128, p, p, 32 * 128 * 2, None)
