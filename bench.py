@@ -9,8 +9,9 @@ all through the C ABI.  Prints ONE JSON line.
                     [--group-size g] [--policy p] [--shared-policy p] [--no-graph] [--no-cpu-baseline]
 
 The timed region runs the K steps twice: once eagerly with HIP events around each grouped-GEMM
-launch (these give the per-kernel durations the roofline figures use), and once as replays of a
-HIP graph of the same step (no host launch cost between kernels).  `value` comes from the graph
+launch (these give the per-kernel durations the roofline figures use; one stream, one kernel at a
+time), and once as replays of a HIP graph of the same step (no host launch cost between kernels;
+for the decode workload the shared expert runs on a second stream inside the graph).  `value` comes from the graph
 replays unless --no-graph is given; both step times are in the JSON line.
 """
 from __future__ import annotations
@@ -51,6 +52,9 @@ def main() -> int:
     ap.add_argument("--policy", type=int, default=0)
     ap.add_argument("--shared-policy", type=int, default=0)
     ap.add_argument("--no-graph", action="store_true")
+    ap.add_argument("--overlap-shared", type=int, default=-1,
+                    help="1: shared expert on a second stream, concurrent with the routed path; 0: one stream; "
+                         "-1: on for the decode workload (bandwidth-bound kernels that leave CUs free)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     args = ap.parse_args()
@@ -84,7 +88,16 @@ def main() -> int:
     GU, DN = 0x100, 0x200
     names = ["routed_gateup", "routed_down", "shared_gateup", "shared_down"]
 
+    overlap = (args.workload == "decode") if args.overlap_shared < 0 else bool(args.overlap_shared)
+    overlap = overlap and shared is not None
+    side_stream = torch.cuda.Stream() if overlap else None
+
     def step(events=None):
+        if overlap and events is None:       # shared expert (depends on x only) on the second stream
+            main = torch.cuda.current_stream()
+            side_stream.wait_stream(main)
+            with torch.cuda.stream(side_stream):
+                moe.moe_shared_forward(g.x, *shared, buf.S, buf.sg, buf.workspace_shared, args.shared_policy)
         route()
         moe.moe_permute(buf.topk_ids, g.x, s.E, buf.expert_offsets, buf.src_of_row, buf.row_of_pair, buf.Xp,
                         buf.workspace_permute)
@@ -92,8 +105,10 @@ def main() -> int:
             for lo, hi in groups:
                 moe.moe_expert_group_forward(lo, hi, buf.Xp, buf.expert_offsets, g.Wg, g.Wu, g.Wd, buf.Yp,
                                              buf.workspace, args.policy)
-            if shared is not None:
+            if shared is not None and not overlap:
                 moe.moe_shared_forward(g.x, *shared, buf.S, buf.sg, buf.workspace_shared, args.shared_policy)
+            if overlap:
+                torch.cuda.current_stream().wait_stream(side_stream)
         else:
             # same kernels, launched one per call so that events can bracket each of them
             ev = [[torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)] for _ in names]
@@ -201,6 +216,7 @@ def main() -> int:
                    "E": s.E, "K": s.K, "I": s.I, "Is": s.Is, "renorm": s.renorm, "expert_blocks": len(groups),
                    "policy": args.policy, "shared_policy": args.shared_policy,
                    "launch": "hip graph replay" if graph_ms is not None else "eager",
+                   "shared_expert_stream": "second stream, concurrent with the routed path" if overlap else "same stream",
                    "active_experts": active, "rows_per_expert_max": int(counts.max()),
                    "rows_per_expert_median": float(np.median(counts))},
         "ms_per_step_eager": eager_ms, "ms_per_step_graph": graph_ms,

@@ -134,7 +134,9 @@ int moe_combine(const void* Yp, const int32_t* row_of_pair, const float* topk_w,
  * (measurement and tuning).  policy: 0 = automatic (what the plain calls use); 1 = weight-streaming
  * kernels, one 16-row weight block per wave; 2 = weight-streaming kernels with K split over the 4
  * waves of a workgroup; 3 = MFMA tiles of 128 token rows, two workgroups per CU; 4 = MFMA tiles of
- * 256 token rows; 5 = MFMA tiles of 128 token rows, one workgroup per CU.
+ * 256 token rows; 5 = MFMA tiles of 128 token rows, one workgroup per CU; 6 = weight-streaming
+ * kernels, the 4 waves share a weight block and split the token rows; 7 = weight-streaming kernels,
+ * two-way token split times two-way K split.
  * Every policy computes the same function; results may differ in the last bf16 bit between
  * policies because the fp32 summation order differs.  Use one policy for all blocks of a layer.
  * Adding 0x100 to policy runs only the first kernel of the call (gate/up projections and SwiGLU

@@ -215,17 +215,25 @@ class LayerBuffers:
 def moe_layer_forward(x, Wr, bias, Wg, Wu, Wd, shared, K: int, renorm: bool,
                       groups: Optional[Sequence[Tuple[int, int]]] = None, buf: Optional[LayerBuffers] = None,
                       tenant_rows: Optional[List[Tuple[int, int]]] = None, policy: int = 0,
-                      shared_policy: int = 0) -> LayerBuffers:
+                      shared_policy: int = 0, shared_stream: Optional[torch.cuda.Stream] = None) -> LayerBuffers:
     """One MoE layer in the paper's order: gating, micro-batch construction, one call per expert
     block, shared expert, aggregation.  Sequencing only; every step is a library call.
 
     shared: (Wsg, Wsu, Wsd, wgate) or None.  groups: expert blocks (lo, hi), default one block.
-    tenant_rows with a [n_tenants, E] bias: gating is called once per tenant slice."""
+    tenant_rows with a [n_tenants, E] bias: gating is called once per tenant slice.
+    shared_stream: run the shared expert on this stream, concurrently with gating, permutation and
+    the routed blocks (it depends on x only); the aggregation waits for it."""
     T, H = x.shape
     E, I, _ = Wg.shape
     Is = 0 if shared is None else shared[0].shape[0]
     if buf is None:
         buf = LayerBuffers.allocate(T, H, E, K, I, Is, x.device)
+    main = torch.cuda.current_stream()
+    if shared is not None and shared_stream is not None:
+        shared_stream.wait_stream(main)
+        with torch.cuda.stream(shared_stream):
+            moe_shared_forward(x, shared[0], shared[1], shared[2], shared[3], buf.S, buf.sg, buf.workspace_shared,
+                               shared_policy)
     if tenant_rows is not None:
         for i, (a, b) in enumerate(tenant_rows):
             moe_route(x[a:b], Wr, None if bias is None else bias[i], K, renorm, buf.topk_ids[a:b], buf.topk_w[a:b])
@@ -235,8 +243,10 @@ def moe_layer_forward(x, Wr, bias, Wg, Wu, Wd, shared, K: int, renorm: bool,
                 buf.workspace_permute)
     for lo, hi in (groups or [(0, E)]):
         moe_expert_group_forward(lo, hi, buf.Xp, buf.expert_offsets, Wg, Wu, Wd, buf.Yp, buf.workspace, policy)
-    if shared is not None:
+    if shared is not None and shared_stream is None:
         moe_shared_forward(x, shared[0], shared[1], shared[2], shared[3], buf.S, buf.sg, buf.workspace_shared,
                            shared_policy)
+    if shared is not None and shared_stream is not None:
+        main.wait_stream(shared_stream)
     moe_combine(buf.Yp, buf.row_of_pair, buf.topk_w, buf.S, buf.sg, buf.out)
     return buf

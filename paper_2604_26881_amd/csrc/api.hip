@@ -15,7 +15,8 @@ bool dims_ok(int H) { return H > 0 && H % 64 == 0; }
 // layer-wide sizes (never the block bounds), so a row's result does not depend on the block cut.
 // policy: 0 = automatic; 1 = streaming, no K split; 2 = streaming, K split over 4 waves;
 //         3 = MFMA tiles of 128 rows, two workgroups per CU; 4 = MFMA tiles of 256 rows;
-//         5 = MFMA tiles of 128 rows, one workgroup per CU.
+//         5 = MFMA tiles of 128 rows, one workgroup per CU; 6 = streaming, the waves split the token
+//         tiles; 7 = streaming, two-way token split times two-way K split.
 // Bits 8 and 9 of the policy word restrict a call to one of its two kernels (0x100: gate/up
 // only, 0x200: down projection only), so that each can be timed on its own.
 struct Plan { bool stream; int ksplit; int tile_rows; bool do_gateup; bool do_down; };
@@ -28,6 +29,8 @@ Plan make_plan(int mean_rows, int n_experts_layer, int policy_word) {
   switch (policy) {
     case 1: p.stream = true; p.ksplit = 1; return p;
     case 2: p.stream = true; p.ksplit = 4; return p;
+    case 6: p.stream = true; p.ksplit = 5; return p;
+    case 7: p.stream = true; p.ksplit = 6; return p;
     case 3: p.stream = false; p.tile_rows = 128; return p;
     case 4: p.stream = false; p.tile_rows = 256; return p;
     case 5: p.stream = false; p.tile_rows = 129; return p;

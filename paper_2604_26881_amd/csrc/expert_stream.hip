@@ -16,10 +16,13 @@
 // the four lanes of a row then cover one full 128-byte line per load pair.
 // Loads for the next K step are issued before the MFMAs of the current one (two register sets).
 //
-// KS = 1: the 4 waves of a workgroup take 4 neighbouring 16-row weight blocks, full K each.
-// KS = 4: the 4 waves split the K steps of one block (step s goes to wave s mod 4) and the partial
-//         sums are added in wave order through LDS; used when there are too few blocks to fill
-//         the chip otherwise.
+// The 4 waves of a workgroup are arranged NBW x MS x KSP (product 4):
+//   NBW  neighbouring 16-row weight blocks, one per wave (plenty of blocks: routed experts);
+//   MS   waves that share one weight block and split the expert's token tiles (many rows, one
+//        expert: the shared expert at decode sizes; the block's weights come from HBM once and
+//        from the L1/L2 for the other waves);
+//   KSP  waves that split the K steps of one block (step s goes to wave s mod KSP); their partial
+//        sums are added in wave order through LDS (too few blocks to fill the chip otherwise).
 #include "common.h"
 
 namespace moe {
@@ -31,12 +34,14 @@ struct StreamFrag {
   u32x4 x[MT][2][2];
 };
 
-template <int MT, int KS, bool GATEUP>
+template <int MT, int NBW, int MS, int KSP, bool GATEUP>
 __global__ __launch_bounds__(256) void expert_stream_kernel(GemmArgs a) {
+  static_assert(NBW * MS * KSP == 4, "four waves per workgroup");
   constexpr int NBR = GATEUP ? 2 : 1;
-  __shared__ float s_red[KS > 1 ? 4 : 1][KS > 1 ? MT * NBR * 4 : 1][64];
+  __shared__ float s_red[KSP > 1 ? 4 : 1][KSP > 1 ? MT * NBR * 4 : 1][64];
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int nb_w = wave % NBW, ms_w = (wave / NBW) % MS, ks_w = wave / (NBW * MS);
   const int y = blockIdx.y;
   const int eg = a.offsets ? a.lo + y : 0;
   const int rb = a.offsets ? a.offsets[a.lo + y] : 0;
@@ -45,24 +50,25 @@ __global__ __launch_bounds__(256) void expert_stream_kernel(GemmArgs a) {
   if (Me <= 0) return;                         // whole workgroup: no barrier is skipped by part of it
 
   const int N = a.N, Kdim = a.Kdim;
-  const int nb = KS == 1 ? (int)blockIdx.x * 4 + wave : (int)blockIdx.x;
+  const int nb = (int)blockIdx.x * NBW + nb_w;
   const int n0 = nb * 16;
-  if (KS == 1 && n0 >= N) return;              // KS == 1 uses no barrier
+  if (KSP == 1 && n0 >= N) return;             // without a K split there is no barrier
   const int kg = lane >> 4, r16 = lane & 15;
   const size_t wrow = (size_t)eg * N + min(n0 + r16, N - 1);
   const bf16_t* wg = a.B0 + wrow * Kdim + 16 * kg;
   const bf16_t* wu = GATEUP ? a.B1 + wrow * Kdim + 16 * kg : nullptr;
 
   const int npairs = (Kdim + 127) / 128;       // K steps of 64 come in pairs
-  const int p_begin = KS == 1 ? 0 : wave;
-  const int p_stride = KS == 1 ? 1 : 4;
+  const int p_begin = ks_w;
+  const int p_stride = KSP;
 
-  for (int m0 = 0; m0 < Me; m0 += 16 * MT) {
-    const int mtv = min(MT, (Me - m0 + 15) / 16);
+  for (int m0 = 0; m0 < Me; m0 += 16 * MT * MS) {
+    const int mw = m0 + ms_w * 16 * MT;        // first row of this wave's token tiles
+    const int mtv = max(0, min(MT, (Me - mw + 15) / 16));
     const bf16_t* xr[MT];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt)
-      xr[mt] = a.A + (size_t)(rb + min(m0 + mt * 16 + r16, Me - 1)) * Kdim + 16 * kg;
+      xr[mt] = a.A + (size_t)(rb + min(mw + mt * 16 + r16, Me - 1)) * Kdim + 16 * kg;
 
     f32x4 accg[MT], accu[MT];
 #pragma unroll
@@ -114,23 +120,25 @@ __global__ __launch_bounds__(256) void expert_stream_kernel(GemmArgs a) {
       }
     };
 
-    StreamFrag<MT, GATEUP> f0, f1;
-    int p = p_begin;
-    if (p < npairs) load(f0, p);
-    while (p < npairs) {
-      const int p1 = p + p_stride, p2 = p + 2 * p_stride;
-      if (p1 < npairs) load(f1, p1);
-      mma(f0, p);
-      if (p1 < npairs) {
-        if (p2 < npairs) load(f0, p2);
-        mma(f1, p1);
+    if (mtv > 0) {
+      StreamFrag<MT, GATEUP> f0, f1;
+      int p = p_begin;
+      if (p < npairs) load(f0, p);
+      while (p < npairs) {
+        const int p1 = p + p_stride, p2 = p + 2 * p_stride;
+        if (p1 < npairs) load(f1, p1);
+        mma(f0, p);
+        if (p1 < npairs) {
+          if (p2 < npairs) load(f0, p2);
+          mma(f1, p1);
+        }
+        p = p2;
       }
-      p = p2;
     }
 
     // accumulator element j of tile mt: output column n0 + 4*(lane/16) + j, token row lane%16
     auto store_tile = [&](int mt, const f32x4& g, const f32x4& u) {
-      const int m = m0 + mt * 16 + r16;
+      const int m = mw + mt * 16 + r16;
       const int n = n0 + 4 * kg;
       if (m < Me && n < N) {
         float v[4];
@@ -143,7 +151,7 @@ __global__ __launch_bounds__(256) void expert_stream_kernel(GemmArgs a) {
       }
     };
 
-    if (KS == 1) {
+    if (KSP == 1) {
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt)
         if (mt < mtv) store_tile(mt, accg[mt], accu[mt]);
@@ -157,17 +165,20 @@ __global__ __launch_bounds__(256) void expert_stream_kernel(GemmArgs a) {
         }
       }
       __syncthreads();
+      // the KSP waves of one (weight block, token split) add up in wave order; tile mt is finished
+      // by the wave of that group whose K-split index is mt % KSP
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) {
-        if (mt < mtv && (mt & 3) == wave) {
+        if (mt < mtv && (mt % KSP) == ks_w) {
           f32x4 g, u;
 #pragma unroll
           for (int j = 0; j < 4; ++j) {
             float sg_ = 0.f, su_ = 0.f;
 #pragma unroll
-            for (int w = 0; w < 4; ++w) {             // fixed order: wave 0,1,2,3
-              sg_ += s_red[w][(mt * NBR + 0) * 4 + j][lane];
-              if (GATEUP) su_ += s_red[w][(mt * NBR + NBR - 1) * 4 + j][lane];
+            for (int w = 0; w < KSP; ++w) {             // fixed order of the K slices
+              const int src = nb_w + NBW * (ms_w + MS * w);
+              sg_ += s_red[src][(mt * NBR + 0) * 4 + j][lane];
+              if (GATEUP) su_ += s_red[src][(mt * NBR + NBR - 1) * 4 + j][lane];
             }
             g[j] = sg_;
             u[j] = su_;
@@ -180,33 +191,47 @@ __global__ __launch_bounds__(256) void expert_stream_kernel(GemmArgs a) {
   }
 }
 
-template <int MT, int KS, bool GATEUP>
+template <int MT, int NBW, int MS, int KSP, bool GATEUP>
 static int launch_stream_t(const GemmArgs& a, hipStream_t st) {
   const int nexp = a.offsets ? a.hi - a.lo : 1;
   const int nblocks = (a.N + 15) / 16;
-  const int gx = KS == 1 ? (nblocks + 3) / 4 : nblocks;
+  const int gx = (nblocks + NBW - 1) / NBW;
   if (gx <= 0 || nexp <= 0) return 0;
-  hipLaunchKernelGGL((expert_stream_kernel<MT, KS, GATEUP>), dim3(gx, nexp), dim3(256), 0, st, a);
+  hipLaunchKernelGGL((expert_stream_kernel<MT, NBW, MS, KSP, GATEUP>), dim3(gx, nexp), dim3(256), 0, st, a);
   return hipGetLastError() == hipSuccess ? 0 : -4;
 }
 
+// mode: 1 = one weight block per wave; 4 = the waves split K; 5 = the waves split the token tiles;
+//       6 = two-way token split times two-way K split.
 template <bool GATEUP>
-static int launch_stream_any(const GemmArgs& a, int ksplit, hipStream_t st) {
-  // token tiles held in registers: sized for about twice the mean rows per expert
-  // with expert_offsets the rows per expert vary around the mean: leave room for twice the mean
-  const int want = a.offsets ? (2 * a.mean_rows + 15) / 16 : (a.rows_fixed + 15) / 16;
+static int launch_stream_any(const GemmArgs& a, int mode, hipStream_t st) {
+  // token tiles held in registers by a wave.  With expert_offsets the rows per expert vary around
+  // the mean: leave room for twice the mean.
+  const int ms = mode == 5 ? 4 : (mode == 6 ? 2 : 1);
+  const int rows = a.offsets ? 2 * a.mean_rows : a.rows_fixed;
+  const int want = (rows + 16 * ms - 1) / (16 * ms);
   const int mt = want <= 1 ? 1 : (want <= 2 ? 2 : 4);
-  if (ksplit > 1) {
-    if (mt == 1) return launch_stream_t<1, 4, GATEUP>(a, st);
-    if (mt == 2) return launch_stream_t<2, 4, GATEUP>(a, st);
-    return launch_stream_t<4, 4, GATEUP>(a, st);
+  switch (mode) {
+    case 4:
+      if (mt == 1) return launch_stream_t<1, 1, 1, 4, GATEUP>(a, st);
+      if (mt == 2) return launch_stream_t<2, 1, 1, 4, GATEUP>(a, st);
+      return launch_stream_t<4, 1, 1, 4, GATEUP>(a, st);
+    case 5:
+      if (mt == 1) return launch_stream_t<1, 1, 4, 1, GATEUP>(a, st);
+      if (mt == 2) return launch_stream_t<2, 1, 4, 1, GATEUP>(a, st);
+      return launch_stream_t<4, 1, 4, 1, GATEUP>(a, st);
+    case 6:
+      if (mt == 1) return launch_stream_t<1, 1, 2, 2, GATEUP>(a, st);
+      if (mt == 2) return launch_stream_t<2, 1, 2, 2, GATEUP>(a, st);
+      return launch_stream_t<4, 1, 2, 2, GATEUP>(a, st);
+    default:
+      if (mt == 1) return launch_stream_t<1, 4, 1, 1, GATEUP>(a, st);
+      if (mt == 2) return launch_stream_t<2, 4, 1, 1, GATEUP>(a, st);
+      return launch_stream_t<4, 4, 1, 1, GATEUP>(a, st);
   }
-  if (mt == 1) return launch_stream_t<1, 1, GATEUP>(a, st);
-  if (mt == 2) return launch_stream_t<2, 1, GATEUP>(a, st);
-  return launch_stream_t<4, 1, GATEUP>(a, st);
 }
 
-int launch_stream_gateup(const GemmArgs& a, int ksplit, hipStream_t st) { return launch_stream_any<true>(a, ksplit, st); }
-int launch_stream_down(const GemmArgs& a, int ksplit, hipStream_t st) { return launch_stream_any<false>(a, ksplit, st); }
+int launch_stream_gateup(const GemmArgs& a, int mode, hipStream_t st) { return launch_stream_any<true>(a, mode, st); }
+int launch_stream_down(const GemmArgs& a, int mode, hipStream_t st) { return launch_stream_any<false>(a, mode, st); }
 
 }  // namespace moe
