@@ -47,7 +47,8 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="prefill", choices=["prefill", "decode", "tenants"])
+    ap.add_argument("--workload", default="prefill", choices=["prefill", "decode", "tenants", "stack"])
+    ap.add_argument("--layers", type=int, default=24, help="layers of the stack workload")
     ap.add_argument("--group-size", type=int, default=0, help="experts per expert block (0: one block)")
     ap.add_argument("--policy", type=int, default=0)
     ap.add_argument("--shared-policy", type=int, default=0)
@@ -70,43 +71,56 @@ def main() -> int:
     import paper_2604_26881_amd as moe
     moe.load()
 
-    wl = {"prefill": workloads.prefill, "decode": workloads.decode, "tenants": workloads.tenants}[args.workload]()
-    s = wl.shape
-    g = wl.to("cuda")
+    stack = args.workload == "stack"
+    if stack:
+        # 24 Qwen-shaped MoE layers (no attention), independent weights per layer drawn on the GPU
+        # (seed 1000 + layer), T = 2048 tokens, residual add + RMS normalisation between layers
+        s = workloads.Shape(T=2048, **workloads.QWEN)
+        wl = workloads.Workload(name="stack", shape=s, x=workloads.tokens(s.T, s.H, 4242, torch.bfloat16),
+                                **workloads.stack_layer_weights(0, device="cuda"))
+        layer_w = [wl.tensors()] + [workloads.stack_layer_weights(l, device="cuda") for l in range(1, args.layers)]
+        g = wl.to("cuda")
+    else:
+        wl = {"prefill": workloads.prefill, "decode": workloads.decode, "tenants": workloads.tenants}[args.workload]()
+        s = wl.shape
+        g = wl.to("cuda")
+        layer_w = [g.tensors()]
+    n_layers = len(layer_w)
     shared = (g.Wsg, g.Wsu, g.Wsd, g.wgate) if s.Is > 0 else None
+    x_stack = torch.empty_like(g.x) if stack else None
     groups = workloads.partition(s.E, args.group_size) if args.group_size > 0 else [(0, s.E)]
     buf = moe.LayerBuffers.allocate(s.T, s.H, s.E, s.K, s.I, s.Is)
 
-    def route():
+    def route(x, w):
         if wl.tenant_rows is not None:
             for i, (a, b) in enumerate(wl.tenant_rows):
-                moe.moe_route(g.x[a:b], g.Wr, g.bias[i], s.K, s.renorm, buf.topk_ids[a:b], buf.topk_w[a:b])
+                moe.moe_route(x[a:b], w["Wr"], w["bias"][i], s.K, s.renorm, buf.topk_ids[a:b], buf.topk_w[a:b])
         else:
-            moe.moe_route(g.x, g.Wr, g.bias, s.K, s.renorm, buf.topk_ids, buf.topk_w)
+            moe.moe_route(x, w["Wr"], w.get("bias"), s.K, s.renorm, buf.topk_ids, buf.topk_w)
 
     # phase bits of the *_ex policy word: 0x100 = gate/up kernel only, 0x200 = down kernel only
     GU, DN = 0x100, 0x200
     names = ["routed_gateup", "routed_down", "shared_gateup", "shared_down"]
-
     overlap = (args.workload == "decode") if args.overlap_shared < 0 else bool(args.overlap_shared)
     overlap = overlap and shared is not None
     side_stream = torch.cuda.Stream() if overlap else None
 
-    def step(events=None):
+    def layer_step(x, w, events=None):
+        sh = (w["Wsg"], w["Wsu"], w["Wsd"], w["wgate"]) if s.Is > 0 else None
         if overlap and events is None:       # shared expert (depends on x only) on the second stream
             main = torch.cuda.current_stream()
             side_stream.wait_stream(main)
             with torch.cuda.stream(side_stream):
-                moe.moe_shared_forward(g.x, *shared, buf.S, buf.sg, buf.workspace_shared, args.shared_policy)
-        route()
-        moe.moe_permute(buf.topk_ids, g.x, s.E, buf.expert_offsets, buf.src_of_row, buf.row_of_pair, buf.Xp,
+                moe.moe_shared_forward(x, *sh, buf.S, buf.sg, buf.workspace_shared, args.shared_policy)
+        route(x, w)
+        moe.moe_permute(buf.topk_ids, x, s.E, buf.expert_offsets, buf.src_of_row, buf.row_of_pair, buf.Xp,
                         buf.workspace_permute)
         if events is None:
             for lo, hi in groups:
-                moe.moe_expert_group_forward(lo, hi, buf.Xp, buf.expert_offsets, g.Wg, g.Wu, g.Wd, buf.Yp,
+                moe.moe_expert_group_forward(lo, hi, buf.Xp, buf.expert_offsets, w["Wg"], w["Wu"], w["Wd"], buf.Yp,
                                              buf.workspace, args.policy)
-            if shared is not None and not overlap:
-                moe.moe_shared_forward(g.x, *shared, buf.S, buf.sg, buf.workspace_shared, args.shared_policy)
+            if sh is not None and not overlap:
+                moe.moe_shared_forward(x, *sh, buf.S, buf.sg, buf.workspace_shared, args.shared_policy)
             if overlap:
                 torch.cuda.current_stream().wait_stream(side_stream)
         else:
@@ -114,23 +128,31 @@ def main() -> int:
             ev = [[torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)] for _ in names]
             ev[0][0].record()
             for lo, hi in groups:
-                moe.moe_expert_group_forward(lo, hi, buf.Xp, buf.expert_offsets, g.Wg, g.Wu, g.Wd, buf.Yp,
+                moe.moe_expert_group_forward(lo, hi, buf.Xp, buf.expert_offsets, w["Wg"], w["Wu"], w["Wd"], buf.Yp,
                                              buf.workspace, args.policy | GU)
             ev[0][1].record()
             ev[1][0].record()
             for lo, hi in groups:
-                moe.moe_expert_group_forward(lo, hi, buf.Xp, buf.expert_offsets, g.Wg, g.Wu, g.Wd, buf.Yp,
+                moe.moe_expert_group_forward(lo, hi, buf.Xp, buf.expert_offsets, w["Wg"], w["Wu"], w["Wd"], buf.Yp,
                                              buf.workspace, args.policy | DN)
             ev[1][1].record()
-            if shared is not None:
+            if sh is not None:
                 ev[2][0].record()
-                moe.moe_shared_forward(g.x, *shared, buf.S, buf.sg, buf.workspace_shared, args.shared_policy | GU)
+                moe.moe_shared_forward(x, *sh, buf.S, buf.sg, buf.workspace_shared, args.shared_policy | GU)
                 ev[2][1].record()
                 ev[3][0].record()
-                moe.moe_shared_forward(g.x, *shared, buf.S, buf.sg, buf.workspace_shared, args.shared_policy | DN)
+                moe.moe_shared_forward(x, *sh, buf.S, buf.sg, buf.workspace_shared, args.shared_policy | DN)
                 ev[3][1].record()
             events.append(ev)
         moe.moe_combine(buf.Yp, buf.row_of_pair, buf.topk_w, buf.S, buf.sg, buf.out)
+
+    def step(events=None):
+        x = g.x
+        for w in layer_w:
+            layer_step(x, w, events)
+            if stack:                      # residual add + RMS normalisation feeds the next layer
+                moe.moe_residual_norm(x, buf.out, x_stack)
+                x = x_stack
 
     for _ in range(args.warmup):
         step()
@@ -148,7 +170,7 @@ def main() -> int:
     for i, n in enumerate(names):
         if shared is None and i >= 2:
             continue
-        kern_ms[n] = float(np.mean([ev[i][0].elapsed_time(ev[i][1]) for ev in events]))
+        kern_ms[n] = float(np.mean([ev[i][0].elapsed_time(ev[i][1]) for ev in events]))   # per layer
 
     # ---- timed region 2: the same step as HIP-graph replays
     graph_ms = None
@@ -175,6 +197,7 @@ def main() -> int:
     ms = graph_ms if graph_ms is not None else eager_ms
     tokens_per_s = s.T / (ms * 1e-3)
     flop_tok = layer_flops_per_token(s)
+    flop_tok *= n_layers
     layer_tflops = flop_tok * s.T / (ms * 1e-3) / 1e12
 
     # ---- roofline of the dominant grouped-GEMM kernel
@@ -207,12 +230,14 @@ def main() -> int:
                    "gbs": alg_bytes[n] / (kern_ms[n] * 1e-3) / 1e9} for n in kern_ms}
 
     # whole-layer fractions against both roofs (weights of active experts + shared + activations)
-    layer_bytes = sum(alg_bytes[n] for n in kern_ms) + s.E * s.H * 2 + 2 * s.T * s.H * 2 + 2 * P * s.H * 2
+    layer_bytes = (sum(alg_bytes[n] for n in kern_ms) + s.E * s.H * 2 + 2 * s.T * s.H * 2 + 2 * P * s.H * 2) * n_layers
     out = {
         "metric": "moe_layer_tokens_per_s", "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"{args.workload}: Qwen1.5-MoE-2.7B-shaped layer, T={s.T}", "T": s.T, "H": s.H,
+        "config": {"workload": (f"stack: {n_layers} Qwen1.5-MoE-2.7B-shaped MoE layers, T={s.T}" if stack else
+                                f"{args.workload}: Qwen1.5-MoE-2.7B-shaped layer, T={s.T}"), "layers": n_layers,
+                   "T": s.T, "H": s.H,
                    "E": s.E, "K": s.K, "I": s.I, "Is": s.Is, "renorm": s.renorm, "expert_blocks": len(groups),
                    "policy": args.policy, "shared_policy": args.shared_policy,
                    "launch": "hip graph replay" if graph_ms is not None else "eager",
@@ -245,6 +270,9 @@ def main() -> int:
         out["cpu_baseline"] = {"value": done / t_cpu, "unit": "tokens/s", "cores": cores, "kind": "oracle",
                                "sample": f"first {done} tokens of the same batch, float64 per-token definition, "
                                          f"{t_cpu:.1f} s"}
+        if stack:   # one layer was timed; the stack repeats it n_layers times per token
+            out["cpu_baseline"]["value"] /= n_layers
+            out["cpu_baseline"]["sample"] += f"; layer 0 only, divided by {n_layers} layers"
     print(json.dumps(out))
     return 0
 

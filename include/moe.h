@@ -130,6 +130,16 @@ int moe_combine(const void* Yp, const int32_t* row_of_pair, const float* topk_w,
                 const float* sg, int T, int H, int K, void* out, void* stream);
 
 /*
+ * Step between two MoE layers when layers are chained without the attention blocks that sit
+ * between them in the model (Sec. 3: the orchestrator runs, per transformer layer, attention, then
+ * gating and the expert blocks; attention is outside this library):
+ *   u = x[t,:] + y[t,:] (fp32);   out[t,:] = bf16( u / sqrt(mean_h(u^2) + eps) )     no learned scale
+ * It keeps activations bounded over a stack of layers.  x, y, out [T,H] bf16; out may alias x or y;
+ * H <= 8192.
+ */
+int moe_residual_norm(const void* x, const void* y, int T, int H, float eps, void* out, void* stream);
+
+/*
  * The same two calls with the kernel shape picked by the caller instead of by the library
  * (measurement and tuning).  policy: 0 = automatic (what the plain calls use); 1 = weight-streaming
  * kernels, one 16-row weight block per wave; 2 = weight-streaming kernels with K split over the 4

@@ -65,7 +65,7 @@ class Oracle:
         self.lib.oracle_num_threads.restype = ctypes.c_int
         for name in ("oracle_route", "oracle_permute", "oracle_gather", "oracle_expert_group_forward",
                      "oracle_shared_forward", "oracle_combine", "oracle_token_forward",
-                     "oracle_set_num_threads"):
+                     "oracle_set_num_threads", "oracle_residual_norm"):
             getattr(self.lib, name).restype = None
 
     # -- helpers -------------------------------------------------------------------------
@@ -142,6 +142,14 @@ class Oracle:
         sg = None if sg is None else self._real(sg)
         out = np.empty((T, H), self.real)
         self.lib.oracle_combine(_p(Yp), _p(row_of_pair), _p(w), _p(S), _p(sg), T, H, K, _p(out))
+        return out
+
+    def residual_norm(self, x, y, eps=1e-6):
+        """bf16( (x + y) / sqrt(mean((x + y)^2) + eps) ) per row; returns float32 holding bf16 values."""
+        x, y = _f32(x), self._real(y)
+        T, H = x.shape
+        out = np.empty((T, H), np.float32)
+        self.lib.oracle_residual_norm(_p(x), _p(y), T, H, ctypes.c_double(eps), _p(out))
         return out
 
     def token_forward(self, tokens, x, Wr, bias, Wg, Wu, Wd, shared, K, renorm):

@@ -256,6 +256,38 @@ void oracle_combine(const real* Yp, const int32_t* row_of_pair, const float* w, 
   }
 }
 
+/* ------------------------------------------------------ chaining layers (no attention) ------ */
+
+/* Round to bf16 (8 significant bits, round to nearest even) and return the value as a float. */
+static float round_bf16(real v) {
+  float f = (float)v;
+  uint32_t u;
+  memcpy(&u, &f, 4);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  u &= 0xffff0000u;
+  memcpy(&f, &u, 4);
+  return f;
+}
+
+/* u = x[t,:] + y[t,:];  out[t,:] = bf16( u / sqrt(mean_h(u^2) + eps) ): the residual add and RMS
+ * normalisation (no learned scale) placed between two MoE layers when a stack of them is run
+ * without attention.  x [T,H] float (bf16 values), y [T,H] real, out [T,H] float (bf16 values). */
+void oracle_residual_norm(const float* x, const real* y, int T, int H, double eps, float* out) {
+#pragma omp parallel for schedule(static)
+  for (int t = 0; t < T; ++t) {
+    real ss = 0;
+    for (int h = 0; h < H; ++h) {
+      real u = (real)x[(size_t)t * H + h] + y[(size_t)t * H + h];
+      ss += u * u;
+    }
+    real scale = (real)1 / (real)sqrt((double)(ss / (real)H) + eps);
+    for (int h = 0; h < H; ++h) {
+      real u = (real)x[(size_t)t * H + h] + y[(size_t)t * H + h];
+      out[(size_t)t * H + h] = round_bf16(u * scale);
+    }
+  }
+}
+
 /* ---------------------------------------------------------- per-token definition ------ */
 
 /* The layer output for the listed tokens, straight from the definition in the header: no

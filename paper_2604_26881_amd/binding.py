@@ -19,7 +19,7 @@ _LIB = None
 SYMBOLS = ["moe_status_string", "moe_route", "moe_permute", "moe_expert_group_forward",
            "moe_expert_group_forward_ex", "moe_shared_forward", "moe_shared_forward_ex", "moe_combine",
            "moe_permute_workspace_bytes", "moe_expert_workspace_bytes", "moe_shared_workspace_bytes",
-           "moe_workspace_bytes"]
+           "moe_workspace_bytes", "moe_residual_norm"]
 
 
 class MoeError(RuntimeError):
@@ -64,6 +64,8 @@ def load() -> ctypes.CDLL:
     lib.moe_permute_workspace_bytes.argtypes = [c_int, c_int, c_int]
     lib.moe_expert_workspace_bytes.argtypes = [c_int, c_int]
     lib.moe_shared_workspace_bytes.argtypes = [c_int, c_int]
+    lib.moe_residual_norm.restype = c_int
+    lib.moe_residual_norm.argtypes = [c_vp, c_vp, c_int, c_int, ctypes.c_float, c_vp, c_vp]
     lib.moe_workspace_bytes.restype = c_sz
     lib.moe_workspace_bytes.argtypes = [c_int] * 6
     _LIB = lib
@@ -175,6 +177,16 @@ def moe_combine(Yp, row_of_pair, topk_w, S, sg, out=None):
     return out
 
 
+def moe_residual_norm(x, y, out=None, eps: float = 1e-6):
+    T, H = x.shape
+    if out is None:
+        out = torch.empty_like(x)
+    rc = load().moe_residual_norm(_ptr(x, torch.bfloat16, "x"), _ptr(y, torch.bfloat16, "y"), T, H, float(eps),
+                                  _ptr(out, torch.bfloat16, "out"), _stream())
+    _check(rc, "moe_residual_norm")
+    return out
+
+
 @dataclass
 class LayerBuffers:
     """Every output and scratch tensor of one layer forward, allocated once and reused."""
@@ -250,3 +262,27 @@ def moe_layer_forward(x, Wr, bias, Wg, Wu, Wd, shared, K: int, renorm: bool,
         main.wait_stream(shared_stream)
     moe_combine(buf.Yp, buf.row_of_pair, buf.topk_w, buf.S, buf.sg, buf.out)
     return buf
+
+
+def moe_stack_forward(x, layers, K: int, renorm: bool, buf: Optional[LayerBuffers] = None, x_out=None,
+                      eps: float = 1e-6):
+    """A stack of MoE layers without attention: x <- residual_norm(x, MoE_l(x)) for each layer.
+
+    layers: sequence of dicts with Wr, Wg, Wu, Wd and optionally Wsg, Wsu, Wsd, wgate, bias.
+    Everything is enqueued on the current stream; nothing synchronises.  Returns the final
+    activations (x_out if given; x itself is not modified)."""
+    T, H = x.shape
+    first = layers[0]
+    E, I, _ = first["Wg"].shape
+    Is = 0 if first.get("Wsg") is None else first["Wsg"].shape[0]
+    if buf is None:
+        buf = LayerBuffers.allocate(T, H, E, K, I, Is, x.device)
+    cur = x
+    if x_out is None:
+        x_out = torch.empty_like(x)
+    for w in layers:
+        shared = None if w.get("Wsg") is None else (w["Wsg"], w["Wsu"], w["Wsd"], w["wgate"])
+        moe_layer_forward(cur, w["Wr"], w.get("bias"), w["Wg"], w["Wu"], w["Wd"], shared, K, renorm, buf=buf)
+        moe_residual_norm(cur, buf.out, x_out, eps)
+        cur = x_out
+    return x_out

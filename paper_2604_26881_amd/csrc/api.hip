@@ -181,4 +181,11 @@ int moe_combine(const void* Yp, const int32_t* row_of_pair, const float* topk_w,
   return launch_combine(Yp, row_of_pair, topk_w, S, sg, T, H, K, out, (hipStream_t)stream);
 }
 
+int moe_residual_norm(const void* x, const void* y, int T, int H, float eps, void* out, void* stream) {
+  if (T < 0 || !dims_ok(H) || H > 8192 || !(eps >= 0.0f)) return MOE_ERR_SHAPE;
+  if (T == 0) return MOE_OK;
+  if (!x || !y || !out) return MOE_ERR_NULL;
+  return launch_residual_norm(x, y, T, H, eps, out, (hipStream_t)stream);
+}
+
 }  // extern "C"

@@ -73,6 +73,57 @@ __global__ __launch_bounds__(256) void gate_dot_kernel(const bf16_t* __restrict_
   if (lane == 0) sg[t] = a;
 }
 
+// out[t,:] = bf16( u / sqrt(mean_h(u^2) + eps) ),  u = x[t,:] + y[t,:] in fp32: the step between two
+// MoE layers when layers are chained without attention.  One workgroup per token; the row stays in
+// registers between the two passes (H <= 8192).
+__global__ __launch_bounds__(256) void residual_norm_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ y,
+                                                            int H, float eps, bf16_t* __restrict__ out) {
+  __shared__ float s_part[4];
+  const int t = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  float u[4][8];
+  float ss = 0.0f;
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int c = threadIdx.x + 256 * r;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) u[r][i] = 0.0f;
+    if (c < H / 8) {
+      const uint4 a = reinterpret_cast<const uint4*>(x + (size_t)t * H)[c];
+      const uint4 b = reinterpret_cast<const uint4*>(y + (size_t)t * H)[c];
+      u[r][0] = bf16_lo(a.x) + bf16_lo(b.x); u[r][1] = bf16_hi(a.x) + bf16_hi(b.x);
+      u[r][2] = bf16_lo(a.y) + bf16_lo(b.y); u[r][3] = bf16_hi(a.y) + bf16_hi(b.y);
+      u[r][4] = bf16_lo(a.z) + bf16_lo(b.z); u[r][5] = bf16_hi(a.z) + bf16_hi(b.z);
+      u[r][6] = bf16_lo(a.w) + bf16_lo(b.w); u[r][7] = bf16_hi(a.w) + bf16_hi(b.w);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) ss = __builtin_fmaf(u[r][i], u[r][i], ss);
+    }
+  }
+  ss = wave_sum(ss);
+  if (lane == 0) s_part[wave] = ss;
+  __syncthreads();
+  const float total = (s_part[0] + s_part[1]) + (s_part[2] + s_part[3]);
+  const float scale = 1.0f / sqrtf(total / (float)H + eps);
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int c = threadIdx.x + 256 * r;
+    if (c < H / 8) {
+      uint4 o;
+      o.x = pack_bf16x2(u[r][0] * scale, u[r][1] * scale);
+      o.y = pack_bf16x2(u[r][2] * scale, u[r][3] * scale);
+      o.z = pack_bf16x2(u[r][4] * scale, u[r][5] * scale);
+      o.w = pack_bf16x2(u[r][6] * scale, u[r][7] * scale);
+      reinterpret_cast<uint4*>(out + (size_t)t * H)[c] = o;
+    }
+  }
+}
+
+int launch_residual_norm(const void* x, const void* y, int T, int H, float eps, void* out, hipStream_t st) {
+  if (T == 0) return 0;
+  hipLaunchKernelGGL(residual_norm_kernel, dim3(T), dim3(256), 0, st, (const bf16_t*)x, (const bf16_t*)y, H, eps,
+                     (bf16_t*)out);
+  return hipGetLastError() == hipSuccess ? 0 : -4;
+}
+
 int launch_combine(const void* Yp, const int32_t* row_of_pair, const float* w, const void* S, const float* sg,
                    int T, int H, int K, void* out, hipStream_t st) {
   if (T == 0) return 0;

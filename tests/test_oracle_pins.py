@@ -441,3 +441,32 @@ def test_float_build_agrees_with_double_build(oracle64, oracle32):
     assert np.array_equal(a["row_of_pair"], b["row_of_pair"])
     err = np.abs(a["out"] - b["out"]).max() / np.abs(a["out"]).max()
     assert err < 1e-5          # three orders of magnitude under the 2e-2 parity bound
+
+
+# ------------------------------------------------------------------ chaining layers
+
+def test_residual_norm_closed_forms_and_library_rounding(oracle64):
+    H = 64
+    # constant rows: u = c everywhere, mean(u^2) = c^2, out = c / sqrt(c^2 + eps), rounded to bf16
+    for c, d in ((1.0, 0.0), (0.5, 0.25), (-3.0, 1.0)):
+        x = np.full((2, H), c, np.float32)
+        y = np.full((2, H), d, np.float64)
+        u = c + d
+        expect = torch.tensor(u / np.sqrt(u * u + 1e-6), dtype=torch.float32).to(torch.bfloat16).float().item()
+        out = oracle64.residual_norm(x, y, 1e-6)
+        assert np.all(out == np.float32(expect))
+    # random rows against the formula in numpy float64, rounded by torch's bf16 conversion
+    rng = np.random.default_rng(3)
+    x = torch.from_numpy(rng.standard_normal((9, 256)).astype(np.float32)).to(torch.bfloat16).float().numpy()
+    y = rng.standard_normal((9, 256)) * 0.3
+    u = x.astype(np.float64) + y
+    ref = u / np.sqrt((u * u).mean(axis=1, keepdims=True) + 1e-6)
+    ref_bf16 = torch.from_numpy(ref.astype(np.float32)).to(torch.bfloat16).float().numpy()
+    out = oracle64.residual_norm(x, y, 1e-6)
+    # double rounding (float64 -> float32 -> bf16) can move a value by one bf16 step in rare ties only
+    assert np.mean(out != ref_bf16) < 1e-3
+    assert np.abs(out - ref).max() <= 2.0 ** -8 * np.abs(ref).max()
+    # rows come out with unit mean square (up to bf16 rounding)
+    assert np.allclose((out.astype(np.float64) ** 2).mean(axis=1), 1.0, atol=5e-3)
+    # a zero row stays zero (eps keeps the divisor finite)
+    assert np.all(oracle64.residual_norm(np.zeros((1, H), np.float32), np.zeros((1, H)), 1e-6) == 0)

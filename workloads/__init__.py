@@ -79,19 +79,21 @@ class Workload:
 
 def _randn(g: torch.Generator, shape, std: float, dtype: torch.dtype) -> torch.Tensor:
     # drawn in fp32 one leading slice at a time so a 60-expert tensor never needs a 2 GB temporary
+    dev = g.device
     if len(shape) == 3:
-        out = torch.empty(shape, dtype=dtype)
+        out = torch.empty(shape, dtype=dtype, device=dev)
         for e in range(shape[0]):
-            out[e] = (torch.randn(shape[1:], generator=g, dtype=torch.float32) * std).to(dtype)
+            out[e] = (torch.randn(shape[1:], generator=g, dtype=torch.float32, device=dev) * std).to(dtype)
         return out
-    return (torch.randn(shape, generator=g, dtype=torch.float32) * std).to(dtype)
+    return (torch.randn(shape, generator=g, dtype=torch.float32, device=dev) * std).to(dtype)
 
 
 def layer_weights(H: int, E: int, I: int, Is: int, seed: int, std_expert: float, std_router: float,
-                  dtype: torch.dtype) -> Dict[str, Optional[torch.Tensor]]:
+                  dtype: torch.dtype, device: str = "cpu") -> Dict[str, Optional[torch.Tensor]]:
     """Random weights of one MoE layer.  Draw order is fixed: Wr, Wg, Wu, Wd, then the shared
-    expert (Wsg, Wsu, Wsd, wgate) when Is > 0."""
-    g = torch.Generator(device="cpu")
+    expert (Wsg, Wsu, Wsd, wgate) when Is > 0.  device="cpu" (default) gives the same bytes on every
+    machine; a GPU device draws there (for the 26 GB stack, whose bytes no test depends on)."""
+    g = torch.Generator(device=device)
     g.manual_seed(seed)
     w: Dict[str, Optional[torch.Tensor]] = {}
     w["Wr"] = _randn(g, (E, H), std_router, dtype)
@@ -185,11 +187,13 @@ def tenants(seed: int = 3, n_tenants: int = 4, T_per: int = 512, **over) -> Work
     return wl
 
 
-def stack_layer_weights(layer: int, **over) -> Dict[str, Optional[torch.Tensor]]:
+def stack_layer_weights(layer: int, device: str = "cpu", **over) -> Dict[str, Optional[torch.Tensor]]:
     """Weights of layer ``layer`` of the 24-layer stack (seed 1000 + layer)."""
     d = dict(QWEN)
     d.update(over)
-    return layer_weights(d["H"], d["E"], d["I"], d["Is"], 1000 + layer, 0.02, 0.02, torch.bfloat16)
+    d.pop("K", None)
+    d.pop("renorm", None)
+    return layer_weights(d["H"], d["E"], d["I"], d["Is"], 1000 + layer, 0.02, 0.02, torch.bfloat16, device)
 
 
 def partition(E: int, g: int) -> List[Tuple[int, int]]:
