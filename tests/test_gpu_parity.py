@@ -442,3 +442,63 @@ def test_stack_of_layers_teacher_forced(moe, oracle64, shape):
     print(f"[parity] free-running stack {shape}: normalised max err {err:.3e}, relative rms err {rel_rms:.3e}", flush=True)
     assert np.allclose((got ** 2).mean(axis=1), 1.0, atol=2e-2)
     assert rel_rms < 0.1
+
+
+# ------------------------------------------------------------------------------ launch modes
+
+def test_graph_replays_equal_eager(moe):
+    # the whole layer captured once in a HIP graph (shared expert on a second stream inside it) and
+    # replayed several times, with eager work and synchronisations in between: every replay must
+    # reproduce the eager result bit for bit
+    wl = workloads.decode(seed=51, T=64, H=512, E=20, I=256, Is=512).to("cuda")
+    s = wl.shape
+    sh = (wl.Wsg, wl.Wsu, wl.Wsd, wl.wgate)
+    eager = moe.moe_layer_forward(wl.x, wl.Wr, None, wl.Wg, wl.Wu, wl.Wd, sh, s.K, s.renorm)
+    torch.cuda.synchronize()
+    ref_out, ref_ids = eager.out.clone(), eager.topk_ids.clone()
+    buf = moe.LayerBuffers.allocate(s.T, s.H, s.E, s.K, s.I, s.Is)
+    side = torch.cuda.Stream()
+    warm = torch.cuda.Stream()
+    warm.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(warm):
+        moe.moe_layer_forward(wl.x, wl.Wr, None, wl.Wg, wl.Wu, wl.Wd, sh, s.K, s.renorm, buf=buf, shared_stream=side)
+    torch.cuda.current_stream().wait_stream(warm)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        moe.moe_layer_forward(wl.x, wl.Wr, None, wl.Wg, wl.Wu, wl.Wd, sh, s.K, s.renorm, buf=buf, shared_stream=side)
+    for i in range(4):
+        buf.out.fill_(float(i))               # eager work between the replays (a fill kernel, no memset node)
+        buf.Yp.fill_(1.0)
+        buf.topk_ids.fill_(-1)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(buf.topk_ids, ref_ids), f"replay {i}: ids"
+        assert torch.equal(buf.out.view(torch.int16), ref_out.view(torch.int16)), f"replay {i}: out"
+
+
+def test_blocks_on_several_streams_equal_one_stream(moe):
+    # expert blocks are stateless and touch disjoint rows: issued on different streams, in any order,
+    # sharing one workspace, they give the rows one stream gives
+    wl = workloads.prefill(seed=52, T=512, H=256, E=24, I=128, Is=0).to("cuda")
+    s = wl.shape
+    ref = moe.moe_layer_forward(wl.x, wl.Wr, wl.bias, wl.Wg, wl.Wu, wl.Wd, None, s.K, s.renorm)
+    torch.cuda.synchronize()
+    buf = moe.LayerBuffers.allocate(s.T, s.H, s.E, s.K, s.I, 0)
+    moe.moe_route(wl.x, wl.Wr, wl.bias, s.K, s.renorm, buf.topk_ids, buf.topk_w)
+    moe.moe_permute(buf.topk_ids, wl.x, s.E, buf.expert_offsets, buf.src_of_row, buf.row_of_pair, buf.Xp,
+                    buf.workspace_permute)
+    streams = [torch.cuda.Stream() for _ in range(3)]
+    main = torch.cuda.current_stream()
+    for st in streams:
+        st.wait_stream(main)
+    for i, (lo, hi) in enumerate(reversed(workloads.partition(s.E, 5))):
+        with torch.cuda.stream(streams[i % 3]):
+            moe.moe_expert_group_forward(lo, hi, buf.Xp, buf.expert_offsets, wl.Wg, wl.Wu, wl.Wd, buf.Yp, buf.workspace)
+    for st in streams:
+        main.wait_stream(st)
+    moe.moe_combine(buf.Yp, buf.row_of_pair, buf.topk_w, None, None, buf.out)
+    torch.cuda.synchronize()
+    assert torch.equal(buf.Yp.view(torch.int16), ref.Yp.view(torch.int16))
+    assert torch.equal(buf.out.view(torch.int16), ref.out.view(torch.int16))
