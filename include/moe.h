@@ -143,8 +143,8 @@ int moe_residual_norm(const void* x, const void* y, int T, int H, float eps, voi
  * The same two calls with the kernel shape picked by the caller instead of by the library
  * (measurement and tuning).  policy: 0 = automatic (what the plain calls use); 1 = weight-streaming
  * kernels, one 16-row weight block per wave; 2 = weight-streaming kernels with K split over the 4
- * waves of a workgroup; 3 = MFMA tiles of 128 token rows, two workgroups per CU; 4 = MFMA tiles of
- * 256 token rows; 5 = MFMA tiles of 128 token rows, one workgroup per CU; 6 = weight-streaming
+ * waves of a workgroup; 3 and 5 = MFMA tiles of 128 token rows; 4 = MFMA tiles of 256 token
+ * rows; 6 = weight-streaming
  * kernels, the 4 waves share a weight block and split the token rows; 7 = weight-streaming kernels,
  * two-way token split times two-way K split.
  * Every policy computes the same function; results may differ in the last bf16 bit between

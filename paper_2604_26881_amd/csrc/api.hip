@@ -14,8 +14,7 @@ bool dims_ok(int H) { return H > 0 && H % 64 == 0; }
 // Which kernels serve an FFN with `mean_rows` expected rows per expert.  The choice uses only
 // layer-wide sizes (never the block bounds), so a row's result does not depend on the block cut.
 // policy: 0 = automatic; 1 = streaming, no K split; 2 = streaming, K split over 4 waves;
-//         3 = MFMA tiles of 128 rows, two workgroups per CU; 4 = MFMA tiles of 256 rows;
-//         5 = MFMA tiles of 128 rows, one workgroup per CU; 6 = streaming, the waves split the token
+//         3 and 5 = MFMA tiles of 128 rows; 4 = MFMA tiles of 256 rows; 6 = streaming, the waves split the token
 //         tiles; 7 = streaming, two-way token split times two-way K split.
 // Bits 8 and 9 of the policy word restrict a call to one of its two kernels (0x100: gate/up
 // only, 0x200: down projection only), so that each can be timed on its own.

@@ -143,7 +143,7 @@ __global__ __launch_bounds__(256) void expert_stream_kernel(GemmArgs a) {
       if (m < Me && n < N) {
         float v[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) v[j] = GATEUP ? g[j] / (1.0f + __expf(-g[j])) * u[j] : g[j];
+        for (int j = 0; j < 4; ++j) v[j] = GATEUP ? __fdividef(g[j], 1.0f + __expf(-g[j])) * u[j] : g[j];
         uint2 o;
         o.x = pack_bf16x2(v[0], v[1]);
         o.y = pack_bf16x2(v[2], v[3]);

@@ -16,15 +16,17 @@
 // b mod 8; the index walk hands each XCD runs of consecutive tiles that share weight and token
 // panels, so they meet in that XCD's L2.
 //
-// Inside a tile: 4 waves, K steps of 32 through a ring of NS LDS stages.  Both panels are copied
+// Inside a tile: 4 waves, K steps of 64 through a ring of NS LDS stages.  Both panels are copied
 // from global memory straight into LDS (global_load_lds, 16 bytes per lane, no registers in
-// between); NS-1 stages are in flight while one is multiplied, which hides the memory latency a
-// single prefetched stage cannot.  The copies are asynchronous: a wave waits with
-// s_waitcnt vmcnt(n) until only the copies of later stages are outstanding, then one workgroup
-// barrier per K step publishes the stage.  Operand fragments are double-buffered in registers so
-// every LDS read is issued one MFMA group ahead of its use.  Staged rows are 64 bytes (4 chunks of 16); a row's
-// chunks are stored at slot = chunk xor (row/2)%4 so the MFMA operand reads (32 rows, same chunk)
-// are bank-conflict free.  MFMA 32x32x16 bf16 with the WEIGHT rows as the
+// between).  Eight lanes fetch one row's 128 bytes, so every request is a whole cache line: with
+// 64-byte requests the L2-to-LDS path delivered 27 B/clk per CU, with 128-byte requests 47 B/clk
+// (measured), and these kernels live on that path.  NS-1 stages are in flight while one is
+// multiplied.  The copies are asynchronous: a wave waits with s_waitcnt vmcnt(n) until only the
+// copies of later stages are outstanding, then one workgroup barrier per K step publishes the
+// stage.  A stage is multiplied in four 16-wide K slices; operand fragments are double-buffered in
+// registers and every LDS read is issued one slice ahead of its use, between the MFMAs of the
+// slice before.  A row's eight 16-byte chunks are stored at slot = chunk xor row%8 so the MFMA
+// operand reads (32 rows, same chunk) are bank-conflict free.  MFMA 32x32x16 bf16 with the WEIGHT rows as the
 // first operand and the TOKEN rows as the second: a lane then owns 4 consecutive output columns
 // of one token row per accumulator quad, which makes the bf16 stores 8 bytes wide.
 // Rows past the end of an expert are clamped on load (they recompute the expert's last row) and
@@ -35,16 +37,16 @@ namespace moe {
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, bool GATEUP, int NS>
 struct TileShape {
-  static constexpr int BK = 32;
-  static constexpr int ROWB = BK * 2;             // bytes per staged row (4 chunks of 16 bytes)
+  static constexpr int BK = 64;
+  static constexpr int ROWB = BK * 2;             // bytes per staged row (8 chunks of 16 bytes)
   static constexpr int WTM = BM / WAVES_M;        // token rows per wave
   static constexpr int WTN = BN / WAVES_N;        // weight rows per wave
   static constexpr int TB = WTM / 32;             // 32-row token blocks per wave
   static constexpr int NB = WTN / 32;             // 32-row weight blocks per wave
   static constexpr int NBH = GATEUP ? NB / 2 : NB;
   static constexpr int STAGE = (BM + BN) * ROWB;  // bytes per LDS stage
-  static constexpr int NL = (BM + BN) / 64;       // 1 KB (16-row) copies per wave and stage
-  static constexpr int NLA = BM / 64;             // the first NLA of them are token rows
+  static constexpr int NL = (BM + BN) / 32;       // 1 KB (8-row) copies per wave and stage
+  static constexpr int NLA = BM / 32;             // the first NLA of them are token rows
   static constexpr int NF = TB + NB;              // operand fragments per wave and 16-wide K slice
   static constexpr int NM = TB * NB;              // MFMAs per wave and 16-wide K slice
   static constexpr int DIST = NS - 1;             // stages in flight while one is being multiplied
@@ -52,7 +54,8 @@ struct TileShape {
   static_assert(WAVES_M * WAVES_N == 4, "four waves per workgroup");
   static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile is made of 32x32 blocks");
   static_assert(!GATEUP || NB % 2 == 0, "gate and up blocks come in pairs");
-  static_assert(BM % 64 == 0 && BN % 128 == 0, "copies of 16 rows are dealt to 4 waves");
+  static_assert(BM % 32 == 0 && BN % 64 == 0, "copies of 8 rows are dealt to 4 waves");
+  static_assert((NS - 1) * NL < 64, "the wait counter holds 6 bits");
 };
 
 constexpr int TILE_EMAX = 256;
@@ -119,15 +122,15 @@ __global__ __launch_bounds__(256, OCC) void expert_tile_kernel(GemmArgs a) {
   const int Lend = ((totalM + TILE_GM - 1) / TILE_GM) * groupTiles;
 
   const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
-  // copy assignment of this lane inside a 16-row block: row lane/4, 16-byte slot lane%4; the slot
-  // holds chunk (slot xor swz) of the row, swz = (row/2)%4, which spreads the MFMA operand reads
-  // (32 rows at the same chunk) over all banks.
-  const int crow = lane >> 2;
-  const int cchunk = (lane & 3) ^ ((lane >> 3) & 3);
-  // operand reads: row lane%32 of a 32-row block, chunk 2*kk + lane/32
+  // copy assignment of this lane inside an 8-row block: row lane/8, 16-byte slot lane%8; the slot
+  // holds chunk (slot xor row%8) of the row, which spreads the MFMA operand reads (32 rows at the
+  // same chunk) over all banks.
+  const int crow = lane >> 3;
+  const int cchunk = (lane & 7) ^ (lane >> 3);
+  // operand reads: row lane%32 of a 32-row block, chunk 2*kk + lane/32 of the row
   const int frag_row = lane & 31;
   const int frag_half = lane >> 5;
-  const int frag_swz = (lane >> 1) & 3;
+  const int frag_swz = lane & 7;
 
   // Tile walk.  Workgroup b runs on XCD b % 8.  Each XCD takes runs of `run` consecutive tile
   // indices (tiles that share panels), one per workgroup slot; with fewer tiles than slots the runs
@@ -165,7 +168,7 @@ __global__ __launch_bounds__(256, OCC) void expert_tile_kernel(GemmArgs a) {
     uint32_t coff[S::NL];
 #pragma unroll
     for (int i = 0; i < S::NL; ++i) {
-      const int row = (i * 4 + wave) * 16 + crow;       // row inside the stage: tokens first, then weights
+      const int row = (i * 4 + wave) * 8 + crow;        // row inside the stage: tokens first, then weights
       int grow;
       if (i < S::NLA) {
         grow = min(row, rowsValid - 1);
@@ -216,19 +219,19 @@ __global__ __launch_bounds__(256, OCC) void expert_tile_kernel(GemmArgs a) {
         fb_[(j_) % S::NB], fa_[(j_) / S::NB], acc[(j_) % S::NB][(j_) / S::NB], 0, 0, 0);
 #define MOE_TILE_MMA(fa_, fb_)                                                                      \
     { _Pragma("unroll") for (int j = 0; j < S::NM; ++j) MOE_TILE_MFMA1(fa_, fb_, j); }
-    // First half of a stage: multiply slice 0 (set A) and, spread between the MFMAs, read the
-    // fragments of slice 1 into set B.  The scheduling fences pin that interleaving, so no LDS read
-    // is issued in front of an idle matrix pipe.
-#define MOE_TILE_HALF1(stage_)                                                                      \
+    // One K slice: multiply the fragments in set X and, spread between the MFMAs, read the
+    // fragments of slice kk_ of stage_ into set Y.  The scheduling fences pin that interleaving, so
+    // no LDS read is issued in front of an idle matrix pipe.
+#define MOE_TILE_SLICE(faX, fbX, faY, fbY, stage_, kk_)                                             \
     { _Pragma("unroll") for (int j = 0; j < S::NM; ++j) {                                           \
-        MOE_TILE_MFMA1(faA, fbA, j);                                                                \
+        MOE_TILE_MFMA1(faX, fbX, j);                                                                \
         _Pragma("unroll") for (int f = 0; f < S::NF; ++f)                                           \
-          if (f * S::NM / S::NF == j) MOE_TILE_READ1(faB, fbB, stage_, 1, f);                        \
+          if (f * S::NM / S::NF == j) MOE_TILE_READ1(faY, fbY, stage_, kk_, f);                      \
         __builtin_amdgcn_sched_barrier(0x6);                                                        \
-    } __builtin_amdgcn_sched_barrier(0); }
-    // Second half: multiply slice 1 (set B); between the MFMAs first request the copies of the
-    // stage that reuses the buffer just freed (ISSUE_), then read slice 0 of the next stage into set A.
-#define MOE_TILE_HALF2(next_stage_, kt_issue_, st_issue_)                                                    \
+    } }
+    // Last slice of a stage: multiply set B; between the MFMAs first request the copies of the stage
+    // that reuses the buffer just freed, then read slice 0 of the next stage into set A.
+#define MOE_TILE_SLICE_LAST(next_stage_, kt_issue_, st_issue_)                                      \
     { _Pragma("unroll") for (int j = 0; j < S::NM; ++j) {                                           \
         MOE_TILE_MFMA1(faB, fbB, j);                                                                \
         _Pragma("unroll") for (int q = 0; q < S::NL + S::NF; ++q)                                   \
@@ -240,11 +243,10 @@ __global__ __launch_bounds__(256, OCC) void expert_tile_kernel(GemmArgs a) {
     } }
 
     // Pipeline.  All NS stages are requested up front; while stage kt is multiplied, stages
-    // kt+1 .. kt+NS-1 are in flight.  The fragments of the second K slice of a stage are read
-    // while the first slice is multiplied, and the first slice of the NEXT stage is read (after
-    // the barrier that publishes it) while the second slice is multiplied, so neither LDS read
-    // waits in front of an idle matrix pipe.  The barrier between the two slices also tells every
-    // wave that stage kt has been read completely, so its buffer can take the copy of stage kt+NS.
+    // kt+1 .. kt+NS-1 are in flight.  Fragment sets A and B alternate over the four slices of a
+    // stage; slice 0 of the NEXT stage is read (after the barrier that publishes it) while the last
+    // slice is multiplied.  That barrier also tells every wave that stage kt has been read
+    // completely, so its buffer can take the copy of stage kt+NS.
     // (Past the end of K the requests repeat the last K step into a buffer nobody reads again:
     // every iteration then issues the same number of copies and the wait counts stay constant.)
 #pragma unroll
@@ -253,27 +255,34 @@ __global__ __launch_bounds__(256, OCC) void expert_tile_kernel(GemmArgs a) {
     workgroup_barrier();
     bf16x8 faA[S::TB], fbA[S::NB], faB[S::TB], fbB[S::NB];
     MOE_TILE_READ(faA, fbA, 0, 0);
+    int st = 0;                                  // buffer of the stage being multiplied: kt % NS
     for (int kt = 0; kt + 1 < nk; ++kt) {
-      MOE_TILE_HALF1(kt % NS);
-      // this wave has finished reading stage kt once the second-slice fragments are in registers
-      // (the empty asm makes the compiler wait for them)
+      const int st1 = st + 1 == NS ? 0 : st + 1;
+      MOE_TILE_SLICE(faA, fbA, faB, fbB, st, 1);
+      MOE_TILE_SLICE(faB, fbB, faA, fbA, st, 2);
+      MOE_TILE_SLICE(faA, fbA, faB, fbB, st, 3);
+      // this wave has finished reading stage kt once the last-slice fragments are in registers
+      // (the empty asm makes the compiler wait for them; the fence keeps that wait behind the MFMAs)
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int tb = 0; tb < S::TB; ++tb) asm volatile("" : "+v"(faB[tb]));
 #pragma unroll
       for (int nb = 0; nb < S::NB; ++nb) asm volatile("" : "+v"(fbB[nb]));
       wait_copies_but<(S::DIST - 1) * S::NL>();
       workgroup_barrier();  // stage kt+1 is complete for everyone; stage kt is free for everyone
-      MOE_TILE_HALF2((kt + 1) % NS, min(kt + NS, nk - 1), kt % NS);
+      MOE_TILE_SLICE_LAST(st1, min(kt + NS, nk - 1), st);
+      st = st1;
     }
-    MOE_TILE_READ(faB, fbB, (nk - 1) % NS, 1);
-    MOE_TILE_MMA(faA, fbA);
+    MOE_TILE_SLICE(faA, fbA, faB, fbB, st, 1);
+    MOE_TILE_SLICE(faB, fbB, faA, fbA, st, 2);
+    MOE_TILE_SLICE(faA, fbA, faB, fbB, st, 3);
     MOE_TILE_MMA(faB, fbB);
     wait_lds_reads();
     workgroup_barrier();   // the next tile's first copies overwrite stages other waves may still read
 #undef MOE_TILE_READ1
 #undef MOE_TILE_MFMA1
-#undef MOE_TILE_HALF1
-#undef MOE_TILE_HALF2
+#undef MOE_TILE_SLICE
+#undef MOE_TILE_SLICE_LAST
 #undef MOE_TILE_ISSUE1
 #undef MOE_TILE_READ
 #undef MOE_TILE_MMA
@@ -299,7 +308,7 @@ __global__ __launch_bounds__(256, OCC) void expert_tile_kernel(GemmArgs a) {
                 if (GATEUP) {
                   const float g = acc[nb][tb][4 * q + j];
                   const float u = acc[nb + S::NBH][tb][4 * q + j];
-                  v[j] = g / (1.0f + __expf(-g)) * u;
+                  v[j] = __fdividef(g, 1.0f + __expf(-g)) * u;
                 } else {
                   v[j] = acc[nb][tb][4 * q + j];
                 }
@@ -350,8 +359,8 @@ static int launch_tile_t(const GemmArgs& a, hipStream_t st) {
   return hipGetLastError() == hipSuccess ? 0 : -4;
 }
 
-// tile_rows: 256 or 128 token rows per tile (129: 128-row tiles, one workgroup per CU with a deeper
-// ring); 0 = choose from layer-wide sizes only (never from the block bounds).
+// tile_rows: 256 or 128 (129 is accepted as 128) token rows per tile; 0 = choose from layer-wide
+// sizes only (never from the block bounds).
 static int pick_tile_rows(const GemmArgs& a, int tile_rows, int nout, bool down) {
   if (tile_rows != 0) return tile_rows;
   if (a.offsets != nullptr)   // experts of mixed sizes (measured on Zipf-skewed routing)
@@ -361,15 +370,15 @@ static int pick_tile_rows(const GemmArgs& a, int tile_rows, int nout, bool down)
 }
 int launch_tile_gateup(const GemmArgs& a, int tile_rows, hipStream_t st) {
   const int t = pick_tile_rows(a, tile_rows, 128, false);
-  if (t >= 256) return launch_tile_t<256, 256, 2, 2, true, 4, 1>(a, st);
-  if (t == 129) return launch_tile_t<128, 256, 1, 4, true, 4, 1>(a, st);
-  return launch_tile_t<128, 256, 1, 4, true, 3, 2>(a, st);
+  if (t >= 256) return launch_tile_t<256, 256, 2, 2, true, 2, 1>(a, st);
+  if (t == 129) return launch_tile_t<128, 256, 1, 4, true, 3, 1>(a, st);
+  return launch_tile_t<128, 256, 1, 4, true, 3, 1>(a, st);
 }
 int launch_tile_down(const GemmArgs& a, int tile_rows, hipStream_t st) {
   const int t = pick_tile_rows(a, tile_rows, 256, true);
-  if (t >= 256) return launch_tile_t<256, 256, 2, 2, false, 4, 1>(a, st);
-  if (t == 129) return launch_tile_t<128, 256, 1, 4, false, 4, 1>(a, st);
-  return launch_tile_t<128, 256, 1, 4, false, 3, 2>(a, st);
+  if (t >= 256) return launch_tile_t<256, 256, 2, 2, false, 2, 1>(a, st);
+  if (t == 129) return launch_tile_t<128, 256, 1, 4, false, 3, 1>(a, st);
+  return launch_tile_t<128, 256, 1, 4, false, 3, 1>(a, st);
 }
 
 }  // namespace moe
