@@ -110,7 +110,8 @@ int moe_expert_group_forward(int group_lo, int group_hi, const void* Xp,
  *   S[t,:] = ( silu(x[t,:] . Wsg^T) * (x[t,:] . Wsu^T) ) . Wsd^T ;   sg[t] = <x[t,:], wgate>
  *   x [T,H]; Wsg, Wsu [Is,H]; Wsd [H,Is]; wgate [H] (bf16) or NULL (then sg is not written);
  *   S [T,H] bf16; sg [T] fp32.
- * workspace: moe_shared_workspace_bytes(T, Is) bytes.
+ * workspace: moe_shared_workspace_bytes(T, H, Is) bytes (h as bf16 [T,Is]; for T <= 256 also the
+ * fp32 partial sums of a down projection that is cut along K).
  */
 int moe_shared_forward(const void* x, const void* Wsg, const void* Wsu, const void* Wsd,
                        const void* wgate, int T, int H, int Is, void* S, float* sg,
@@ -144,9 +145,12 @@ int moe_residual_norm(const void* x, const void* y, int T, int H, float eps, voi
  * (measurement and tuning).  policy: 0 = automatic (what the plain calls use); 1 = weight-streaming
  * kernels, one 16-row weight block per wave; 2 = weight-streaming kernels with K split over the 4
  * waves of a workgroup; 3 and 5 = MFMA tiles of 128 token rows; 4 = MFMA tiles of 256 token
- * rows; 6 = weight-streaming
- * kernels, the 4 waves share a weight block and split the token rows; 7 = weight-streaming kernels,
- * two-way token split times two-way K split.
+ * rows; 6 = weight-streaming kernels, the 4 waves share a weight block and split the token rows;
+ * 7 = weight-streaming kernels, two-way token split times two-way K split; 8 = MFMA tiles of 128
+ * token rows by 64 weight rows (for the shared expert, whose workspace has room for them, the down
+ * projection is cut into up to 8 parts along K whose fp32 partial sums a second kernel adds in
+ * ascending order; with policy 8 and T > 256 the shared call needs the workspace of
+ * moe_shared_workspace_bytes plus 8*T*H*4 bytes).
  * Every policy computes the same function; results may differ in the last bf16 bit between
  * policies because the fp32 summation order differs.  Use one policy for all blocks of a layer.
  * Adding 0x100 to policy runs only the first kernel of the call (gate/up projections and SwiGLU
@@ -164,7 +168,7 @@ int moe_shared_forward_ex(const void* x, const void* Wsg, const void* Wsu, const
 /* Workspace sizes in bytes (multiples of 256). */
 size_t moe_permute_workspace_bytes(int T, int K, int E);
 size_t moe_expert_workspace_bytes(int P, int I);
-size_t moe_shared_workspace_bytes(int T, int Is);
+size_t moe_shared_workspace_bytes(int T, int H, int Is);
 /* Largest of the three: one buffer of this size serves every call of a layer issued on one
  * stream. */
 size_t moe_workspace_bytes(int T, int H, int E, int K, int I, int Is);

@@ -63,7 +63,7 @@ def load() -> ctypes.CDLL:
         getattr(lib, n).restype = c_sz
     lib.moe_permute_workspace_bytes.argtypes = [c_int, c_int, c_int]
     lib.moe_expert_workspace_bytes.argtypes = [c_int, c_int]
-    lib.moe_shared_workspace_bytes.argtypes = [c_int, c_int]
+    lib.moe_shared_workspace_bytes.argtypes = [c_int, c_int, c_int]
     lib.moe_residual_norm.restype = c_int
     lib.moe_residual_norm.argtypes = [c_vp, c_vp, c_int, c_int, ctypes.c_float, c_vp, c_vp]
     lib.moe_workspace_bytes.restype = c_sz
@@ -211,7 +211,7 @@ class LayerBuffers:
         i32 = dict(dtype=torch.int32, device=device)
         bf = dict(dtype=torch.bfloat16, device=device)
         ws = max(int(lib.moe_expert_workspace_bytes(P, I)), 256)
-        wss = int(lib.moe_shared_workspace_bytes(T, Is))
+        wss = int(lib.moe_shared_workspace_bytes(T, H, Is))
         return LayerBuffers(
             topk_ids=torch.empty((T, K), **i32), topk_w=torch.empty((T, K), dtype=torch.float32, device=device),
             expert_offsets=torch.empty(E + 1, **i32), src_of_row=torch.empty(P, **i32),

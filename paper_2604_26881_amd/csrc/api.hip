@@ -15,7 +15,8 @@ bool dims_ok(int H) { return H > 0 && H % 64 == 0; }
 // layer-wide sizes (never the block bounds), so a row's result does not depend on the block cut.
 // policy: 0 = automatic; 1 = streaming, no K split; 2 = streaming, K split over 4 waves;
 //         3 and 5 = MFMA tiles of 128 rows; 4 = MFMA tiles of 256 rows; 6 = streaming, the waves split the token
-//         tiles; 7 = streaming, two-way token split times two-way K split.
+//         tiles; 7 = streaming, two-way token split times two-way K split; 8 = MFMA tiles of 128 rows
+//         by 64 weight rows, the down projection cut along K (few rows in all, one weight set).
 // Bits 8 and 9 of the policy word restrict a call to one of its two kernels (0x100: gate/up
 // only, 0x200: down projection only), so that each can be timed on its own.
 struct Plan { bool stream; int ksplit; int tile_rows; bool do_gateup; bool do_down; };
@@ -33,6 +34,7 @@ Plan make_plan(int mean_rows, int n_experts_layer, int policy_word) {
     case 3: p.stream = false; p.tile_rows = 128; return p;
     case 4: p.stream = false; p.tile_rows = 256; return p;
     case 5: p.stream = false; p.tile_rows = 129; return p;
+    case 8: p.stream = false; p.tile_rows = 64; return p;
     default: break;
   }
   const bool few_experts = n_experts_layer < 16;   // e.g. the shared expert: one weight set, all rows
@@ -82,15 +84,19 @@ size_t moe_expert_workspace_bytes(int P, int I) {
   if (P <= 0 || I <= 0) return 0;
   return align256((size_t)P * (size_t)I * 2);
 }
-size_t moe_shared_workspace_bytes(int T, int Is) {
-  if (T <= 0 || Is <= 0) return 0;
-  return align256((size_t)T * (size_t)Is * 2);
+// h [T,Is] bf16, then (small batches only) the fp32 partial outputs of a down projection cut along K
+constexpr int SHARED_SMALL_T = 256;
+constexpr int SHARED_KPARTS_MAX = 8;
+size_t moe_shared_workspace_bytes(int T, int H, int Is) {
+  if (T <= 0 || H <= 0 || Is <= 0) return 0;
+  size_t n = align256((size_t)T * (size_t)Is * 2);
+  if (T <= SHARED_SMALL_T) n += (size_t)SHARED_KPARTS_MAX * (size_t)T * (size_t)H * 4;
+  return n;
 }
 size_t moe_workspace_bytes(int T, int H, int E, int K, int I, int Is) {
-  (void)H;
   size_t a = moe_permute_workspace_bytes(T, K, E);
   size_t b = moe_expert_workspace_bytes(T * K, I);
-  size_t c = moe_shared_workspace_bytes(T, Is);
+  size_t c = moe_shared_workspace_bytes(T, H, Is);
   size_t m = a > b ? a : b;
   return m > c ? m : c;
 }
@@ -153,13 +159,19 @@ int moe_shared_forward_ex(const void* x, const void* Wsg, const void* Wsu, const
   if (wgate && !sg) return MOE_ERR_NULL;
   if (workspace_bytes < (size_t)T * (size_t)Is * 2) return MOE_ERR_WORKSPACE;   // h, bf16 [T,Is]
   const Plan plan = make_plan(T, 1, policy);
+  const size_t h_bytes = align256((size_t)T * (size_t)Is * 2);
+  float* part = nullptr;
+  if (!plan.stream && plan.tile_rows == 64 && tile_down_ksplit(Is) > 1) {
+    if (workspace_bytes < h_bytes + (size_t)tile_down_ksplit(Is) * (size_t)T * (size_t)H * 4) return MOE_ERR_WORKSPACE;
+    part = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + h_bytes);
+  }
   GemmArgs gu{};
   gu.A = (const bf16_t*)x; gu.B0 = (const bf16_t*)Wsg; gu.B1 = (const bf16_t*)Wsu; gu.C = (bf16_t*)workspace;
   gu.offsets = nullptr; gu.lo = 0; gu.hi = 1; gu.rows_fixed = T; gu.rows_total = T; gu.mean_rows = T;
   gu.N = Is; gu.Kdim = H;
   GemmArgs dn = gu;
   dn.A = (const bf16_t*)workspace; dn.B0 = (const bf16_t*)Wsd; dn.B1 = nullptr; dn.C = (bf16_t*)S;
-  dn.N = H; dn.Kdim = Is;
+  dn.N = H; dn.Kdim = Is; dn.Cpart = part;
   int rc = ffn_forward(gu, dn, plan, (hipStream_t)stream);
   if (rc != 0) return rc;
   if (wgate && plan.do_down) return launch_gate_dot(x, wgate, T, H, sg, (hipStream_t)stream);

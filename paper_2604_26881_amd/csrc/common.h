@@ -52,6 +52,7 @@ struct GemmArgs {
   int mean_rows;       // expected rows per expert (rows_total / experts of the layer): picks kernel shapes
   int N;               // output columns (per branch for gate/up)
   int Kdim;            // contraction length
+  float* Cpart;        // fp32 partial outputs [parts, rows_total, N] of kernels that cut K, else unused
 };
 
 int launch_route(const void* x, const void* Wr, const float* bias, int T, int H, int E, int K, int renorm,
@@ -65,6 +66,7 @@ int launch_gate_dot(const void* x, const void* wgate, int T, int H, float* sg, h
 // Tiled MFMA kernels (many rows per expert) and streaming kernels (few rows per expert).
 int launch_tile_gateup(const GemmArgs& a, int tile_rows, hipStream_t st);
 int launch_tile_down(const GemmArgs& a, int tile_rows, hipStream_t st);
+int tile_down_ksplit(int Kdim);   // K parts of the down projection when tile_rows == 64
 int launch_stream_gateup(const GemmArgs& a, int ksplit, hipStream_t st);
 int launch_stream_down(const GemmArgs& a, int ksplit, hipStream_t st);
 

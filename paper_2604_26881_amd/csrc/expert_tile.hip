@@ -51,6 +51,7 @@ struct TileShape {
   static constexpr int NM = TB * NB;              // MFMAs per wave and 16-wide K slice
   static constexpr int DIST = NS - 1;             // stages in flight while one is being multiplied
   static constexpr int NOUT = GATEUP ? BN / 2 : BN;  // output columns per tile
+  static constexpr int GM = BN >= 256 ? 4 : 1;    // token tiles per locality group of the tile walk
   static_assert(WAVES_M * WAVES_N == 4, "four waves per workgroup");
   static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile is made of 32x32 blocks");
   static_assert(!GATEUP || NB % 2 == 0, "gate and up blocks come in pairs");
@@ -59,7 +60,6 @@ struct TileShape {
 };
 
 constexpr int TILE_EMAX = 256;
-constexpr int TILE_GM = 4;   // token tiles per locality group
 
 // One 16-byte-per-lane copy from global memory straight into LDS (no registers in between):
 // lane l of the wave writes LDS bytes [lds + 16*l, +16) from global address base + voff.
@@ -75,7 +75,7 @@ __device__ __forceinline__ void wait_copies_but() {   // all but the N most rece
 __device__ __forceinline__ void workgroup_barrier() { asm volatile("s_barrier" ::: "memory"); }
 __device__ __forceinline__ void wait_lds_reads() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, bool GATEUP, int NS, int OCC>
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool GATEUP, int NS, int OCC, int KSPLIT>
 __global__ __launch_bounds__(256, OCC) void expert_tile_kernel(GemmArgs a) {
   using S = TileShape<BM, BN, WAVES_M, WAVES_N, GATEUP, NS>;
   extern __shared__ __align__(16) unsigned char smem[];
@@ -117,9 +117,9 @@ __global__ __launch_bounds__(256, OCC) void expert_tile_kernel(GemmArgs a) {
   const int totalM = s_pref[nexp];
   const int NT = (a.N + S::NOUT - 1) / S::NOUT;
   const int Kdim = a.Kdim;
-  const int nk = Kdim / S::BK;
-  const int groupTiles = TILE_GM * NT;
-  const int Lend = ((totalM + TILE_GM - 1) / TILE_GM) * groupTiles;
+  const int nk = Kdim / S::BK / KSPLIT;          // K steps of one work item (a tile, or a K part of it)
+  const int groupTiles = S::GM * NT;
+  const int Lend = ((totalM + S::GM - 1) / S::GM) * groupTiles * KSPLIT;
 
   const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
   // copy assignment of this lane inside an 8-row block: row lane/8, 16-byte slot lane%8; the slot
@@ -143,9 +143,11 @@ __global__ __launch_bounds__(256, OCC) void expert_tile_kernel(GemmArgs a) {
   for (int it = 0;; ++it) {
     const int L = xcd_walk ? ((it * 8 + (int)(blockIdx.x & 7)) * run + slot) : (it * G + (int)blockIdx.x);
     if (L >= Lend) break;
-    const int grp = L / groupTiles, rem = L - grp * groupTiles;
-    const int mrow = grp * TILE_GM + rem % TILE_GM;
-    const int nt = rem / TILE_GM;
+    const int ks = KSPLIT > 1 ? L % KSPLIT : 0;   // K part of this work item
+    const int Lt = KSPLIT > 1 ? L / KSPLIT : L;
+    const int grp = Lt / groupTiles, rem = Lt - grp * groupTiles;
+    const int mrow = grp * S::GM + rem % S::GM;
+    const int nt = rem / S::GM;
     if (mrow >= totalM) continue;
 
     // expert of this token tile: last e with s_pref[e] <= mrow
@@ -161,9 +163,10 @@ __global__ __launch_bounds__(256, OCC) void expert_tile_kernel(GemmArgs a) {
     const int n0 = nt * S::NOUT;
     const int eg = a.offsets ? a.lo + e : 0;
 
-    const unsigned char* Ag = reinterpret_cast<const unsigned char*>(a.A + (size_t)row0 * Kdim);
-    const unsigned char* Bg0 = reinterpret_cast<const unsigned char*>(a.B0 + (size_t)eg * a.N * Kdim);
-    const unsigned char* Bg1 = GATEUP ? reinterpret_cast<const unsigned char*>(a.B1 + (size_t)eg * a.N * Kdim) : nullptr;
+    const size_t kbeg = (size_t)ks * nk * S::BK;
+    const unsigned char* Ag = reinterpret_cast<const unsigned char*>(a.A + (size_t)row0 * Kdim + kbeg);
+    const unsigned char* Bg0 = reinterpret_cast<const unsigned char*>(a.B0 + (size_t)eg * a.N * Kdim + kbeg);
+    const unsigned char* Bg1 = GATEUP ? reinterpret_cast<const unsigned char*>(a.B1 + (size_t)eg * a.N * Kdim + kbeg) : nullptr;
     // byte offsets of this lane's 16 bytes for each of the NL copies of a stage (K step 0)
     uint32_t coff[S::NL];
 #pragma unroll
@@ -313,10 +316,15 @@ __global__ __launch_bounds__(256, OCC) void expert_tile_kernel(GemmArgs a) {
                   v[j] = acc[nb][tb][4 * q + j];
                 }
               }
-              uint2 o;
-              o.x = pack_bf16x2(v[0], v[1]);
-              o.y = pack_bf16x2(v[2], v[3]);
-              *reinterpret_cast<uint2*>(crow_out + n) = o;
+              if (KSPLIT > 1) {   // fp32 partial sum of K part ks; summed in order by the reduce kernel
+                float* part = a.Cpart + ((size_t)ks * a.rows_total + m) * a.N + n;
+                *reinterpret_cast<float4*>(part) = make_float4(v[0], v[1], v[2], v[3]);
+              } else {
+                uint2 o;
+                o.x = pack_bf16x2(v[0], v[1]);
+                o.y = pack_bf16x2(v[2], v[3]);
+                *reinterpret_cast<uint2*>(crow_out + n) = o;
+              }
             }
           }
         }
@@ -336,10 +344,30 @@ static int num_cus() {
   return cus;
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, bool GATEUP, int NS, int OCC>
+// Sum of the KSPLIT fp32 partial outputs in ascending K part, rounded once to bf16.
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ part, int ksplit, long n4, long stride4,
+                                                            bf16_t* __restrict__ C) {
+  const long i = (long)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n4) return;
+  const float4* p = reinterpret_cast<const float4*>(part);
+  float4 s = p[i];
+  for (int k = 1; k < ksplit; ++k) {
+    const float4 v = p[i + (long)k * stride4];
+    s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+  }
+  uint2 o;
+  o.x = pack_bf16x2(s.x, s.y);
+  o.y = pack_bf16x2(s.z, s.w);
+  reinterpret_cast<uint2*>(C)[i] = o;
+}
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, bool GATEUP, int NS, int OCC, int KSPLIT = 1>
 static int launch_tile_t(const GemmArgs& a, hipStream_t st) {
   using S = TileShape<BM, BN, WAVES_M, WAVES_N, GATEUP, NS>;
-  auto kern = expert_tile_kernel<BM, BN, WAVES_M, WAVES_N, GATEUP, NS, OCC>;
+  auto kern = expert_tile_kernel<BM, BN, WAVES_M, WAVES_N, GATEUP, NS, OCC, KSPLIT>;
+  static_assert(KSPLIT == 1 || !GATEUP, "the SwiGLU product needs complete sums");
+  if (a.Kdim % (S::BK * KSPLIT) != 0) return -2;
+  if (KSPLIT > 1 && a.Cpart == nullptr) return -3;
   static_assert(OCC * (NS * S::STAGE + 2100) <= 160 * 1024, "LDS of the resident workgroups must fit a CU");
   static bool attr_set = false;
   const int lds = NS * S::STAGE;
@@ -350,17 +378,25 @@ static int launch_tile_t(const GemmArgs& a, hipStream_t st) {
   const int nexp = a.offsets ? a.hi - a.lo : 1;
   const int NT = (a.N + S::NOUT - 1) / S::NOUT;
   const long mt_bound = (long)a.rows_total / BM + nexp;
-  const long bound = ((mt_bound + TILE_GM - 1) / TILE_GM) * TILE_GM * NT;
+  const long bound = ((mt_bound + S::GM - 1) / S::GM) * S::GM * NT * KSPLIT;
   // persistent workgroups: as many as fit on the chip at once (two per CU for the smaller tile)
   const long resident = (long)num_cus() * OCC;
   int grid = (int)(bound < resident ? bound : resident);
   if (grid <= 0) return 0;
   hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, st, a);
-  return hipGetLastError() == hipSuccess ? 0 : -4;
+  if (hipGetLastError() != hipSuccess) return -4;
+  if (KSPLIT > 1) {
+    const long n4 = (long)a.rows_total * a.N / 4;
+    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, st, a.Cpart, KSPLIT, n4, n4, a.C);
+    if (hipGetLastError() != hipSuccess) return -4;
+  }
+  return 0;
 }
 
-// tile_rows: 256 or 128 (129 is accepted as 128) token rows per tile; 0 = choose from layer-wide
-// sizes only (never from the block bounds).
+// tile_rows: 256 or 128 (129 is accepted as 128) token rows per tile; 64 = 128 token rows by 64 weight
+// rows (few rows in all: many small tiles so that every CU streams a share of the weights; the down
+// projection is also cut along K and its parts are summed in order by a second kernel);
+// 0 = choose from layer-wide sizes only (never from the block bounds).
 static int pick_tile_rows(const GemmArgs& a, int tile_rows, int nout, bool down) {
   if (tile_rows != 0) return tile_rows;
   if (a.offsets != nullptr)   // experts of mixed sizes (measured on Zipf-skewed routing)
@@ -370,14 +406,22 @@ static int pick_tile_rows(const GemmArgs& a, int tile_rows, int nout, bool down)
 }
 int launch_tile_gateup(const GemmArgs& a, int tile_rows, hipStream_t st) {
   const int t = pick_tile_rows(a, tile_rows, 128, false);
+  if (t == 64) return launch_tile_t<128, 64, 4, 1, true, 6, 1>(a, st);
   if (t >= 256) return launch_tile_t<256, 256, 2, 2, true, 2, 1>(a, st);
-  if (t == 129) return launch_tile_t<128, 256, 1, 4, true, 3, 1>(a, st);
   return launch_tile_t<128, 256, 1, 4, true, 3, 1>(a, st);
 }
+int tile_down_ksplit(int Kdim) { return Kdim % 512 == 0 ? 8 : Kdim % 256 == 0 ? 4 : Kdim % 128 == 0 ? 2 : 1; }
 int launch_tile_down(const GemmArgs& a, int tile_rows, hipStream_t st) {
   const int t = pick_tile_rows(a, tile_rows, 256, true);
+  if (t == 64) {
+    switch (a.Cpart ? tile_down_ksplit(a.Kdim) : 1) {   // without a buffer for the parts: whole K per tile
+      case 8: return launch_tile_t<128, 64, 4, 1, false, 6, 1, 8>(a, st);
+      case 4: return launch_tile_t<128, 64, 4, 1, false, 6, 1, 4>(a, st);
+      case 2: return launch_tile_t<128, 64, 4, 1, false, 6, 1, 2>(a, st);
+      default: return launch_tile_t<128, 64, 4, 1, false, 6, 1, 1>(a, st);
+    }
+  }
   if (t >= 256) return launch_tile_t<256, 256, 2, 2, false, 2, 1>(a, st);
-  if (t == 129) return launch_tile_t<128, 256, 1, 4, false, 3, 1>(a, st);
   return launch_tile_t<128, 256, 1, 4, false, 3, 1>(a, st);
 }
 

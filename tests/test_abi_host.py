@@ -39,7 +39,9 @@ def test_status_strings(lib):
 def test_workspace_sizes(lib):
     P, I, T, Is = 16384, 1408, 4096, 5632
     assert lib.moe_expert_workspace_bytes(P, I) == P * I * 2
-    assert lib.moe_shared_workspace_bytes(T, Is) == T * Is * 2
+    assert lib.moe_shared_workspace_bytes(T, 2048, Is) == T * Is * 2
+    # small batches: room for the fp32 partial sums of a down projection cut into 8 parts along K
+    assert lib.moe_shared_workspace_bytes(128, 2048, Is) == 128 * Is * 2 + 8 * 128 * 2048 * 4
     assert lib.moe_expert_workspace_bytes(3, 64) % 256 == 0 and lib.moe_expert_workspace_bytes(3, 64) >= 3 * 64 * 2
     assert lib.moe_workspace_bytes(T, 2048, 60, 4, I, Is) == max(P * I * 2, T * Is * 2)
     assert lib.moe_permute_workspace_bytes(T, 4, 60) == (P // 64) * 60 * 4

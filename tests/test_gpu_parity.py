@@ -209,7 +209,7 @@ def test_expert_blocks_match_oracle(moe, oracle64, policy):
     check_close(f64(out), ref["out"], f"layer output policy {policy}")
 
 
-@pytest.mark.parametrize("policy", [0, 1, 2, 3, 4, 5, 6, 7])
+@pytest.mark.parametrize("policy", [0, 1, 2, 3, 4, 5, 6, 7, 8])
 @pytest.mark.parametrize("T", [5, 130, 300])
 def test_shared_expert_matches_oracle(moe, oracle64, policy, T):
     wl = workloads.decode(seed=31, T=T, H=256, E=8, I=64, Is=448)
@@ -223,6 +223,26 @@ def test_shared_expert_matches_oracle(moe, oracle64, policy, T):
     torch.cuda.synchronize()
     check_close(f64(S), S_ref, f"shared expert T={T} policy {policy}")
     assert np.allclose(sg.cpu().numpy(), sg_ref, rtol=1e-4, atol=1e-5)
+
+
+@pytest.mark.parametrize("Is", [448, 640, 768, 1024])     # down projection in 1, 2, 4 and 8 parts along K
+@pytest.mark.parametrize("T", [5, 130, 300])
+def test_shared_expert_small_tiles_match_oracle(moe, oracle64, T, Is):
+    wl = workloads.decode(seed=37, T=T, H=256, E=8, I=64, Is=Is)
+    d = wl.f32_numpy()
+    S_ref, sg_ref = oracle64.shared_forward(d["x"], d["Wsg"], d["Wsu"], d["Wsd"], d["wgate"])
+    g = wl.to("cuda")
+    S = torch.full((T, 256), 768.0, dtype=torch.bfloat16, device="cuda")
+    sg = torch.empty(T, dtype=torch.float32, device="cuda")
+    h_bytes = (T * Is * 2 + 255) // 256 * 256
+    ws = torch.empty(h_bytes + 8 * T * 256 * 4, dtype=torch.uint8, device="cuda")
+    moe.moe_shared_forward(g.x, g.Wsg, g.Wsu, g.Wsd, g.wgate, S, sg, ws, 8)
+    torch.cuda.synchronize()
+    check_close(f64(S), S_ref, f"shared expert, small tiles, T={T} Is={Is}")
+    assert np.allclose(sg.cpu().numpy(), sg_ref, rtol=1e-4, atol=1e-5)
+    if Is == 1024:   # without room for the partial sums the call is refused, nothing is launched
+        with pytest.raises(moe.MoeError):
+            moe.moe_shared_forward(g.x, g.Wsg, g.Wsu, g.Wsd, g.wgate, S, sg, ws[:h_bytes], 8)
 
 
 def test_combine_matches_oracle(moe, oracle64):
