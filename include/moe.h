@@ -110,7 +110,7 @@ int moe_expert_group_forward(int group_lo, int group_hi, const void* Xp,
  *   S[t,:] = ( silu(x[t,:] . Wsg^T) * (x[t,:] . Wsu^T) ) . Wsd^T ;   sg[t] = <x[t,:], wgate>
  *   x [T,H]; Wsg, Wsu [Is,H]; Wsd [H,Is]; wgate [H] (bf16) or NULL (then sg is not written);
  *   S [T,H] bf16; sg [T] fp32.
- * workspace: moe_shared_workspace_bytes(T, H, Is) bytes (h as bf16 [T,Is]; for T <= 256 also the
+ * workspace: moe_shared_workspace_bytes(T, H, Is) bytes (h as bf16 [T,Is]; for T <= 512 also the
  * fp32 partial sums of a down projection that is cut along K).
  */
 int moe_shared_forward(const void* x, const void* Wsg, const void* Wsu, const void* Wsd,
@@ -149,7 +149,7 @@ int moe_residual_norm(const void* x, const void* y, int T, int H, float eps, voi
  * 7 = weight-streaming kernels, two-way token split times two-way K split; 8 = MFMA tiles of 128
  * token rows by 64 weight rows (for the shared expert, whose workspace has room for them, the down
  * projection is cut into up to 8 parts along K whose fp32 partial sums a second kernel adds in
- * ascending order; with policy 8 and T > 256 the shared call needs the workspace of
+ * ascending order; with policy 8 and T > 512 the shared call needs the workspace of
  * moe_shared_workspace_bytes plus 8*T*H*4 bytes).
  * Every policy computes the same function; results may differ in the last bf16 bit between
  * policies because the fp32 summation order differs.  Use one policy for all blocks of a layer.

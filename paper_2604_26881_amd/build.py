@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libmoe_hip.so")
 OBJDIR = os.path.join(HERE, "_build")
-SOURCES = ["api.hip", "route.hip", "permute.hip", "combine.hip", "expert_tile.hip", "expert_stream.hip"]
+SOURCES = ["api.hip", "route.hip", "permute.hip", "combine.hip", "expert_tile.hip", "expert_stream.hip", "expert_stream_lds.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          # packed-fp32 instructions are switched off for all device code

@@ -16,9 +16,13 @@ bool dims_ok(int H) { return H > 0 && H % 64 == 0; }
 // policy: 0 = automatic; 1 = streaming, no K split; 2 = streaming, K split over 4 waves;
 //         3 and 5 = MFMA tiles of 128 rows; 4 = MFMA tiles of 256 rows; 6 = streaming, the waves split the token
 //         tiles; 7 = streaming, two-way token split times two-way K split; 8 = MFMA tiles of 128 rows
-//         by 64 weight rows, the down projection cut along K (few rows in all, one weight set).
+//         by 64 weight rows, the down projection cut along K (few rows in all, one weight set);
+//         9 = streaming through wave-private LDS rings (whole-line requests).
 // Bits 8 and 9 of the policy word restrict a call to one of its two kernels (0x100: gate/up
 // only, 0x200: down projection only), so that each can be timed on its own.
+constexpr int SHARED_SMALL_T = 512;     // up to here the shared expert runs on the 128x64 tiles
+constexpr int SHARED_KPARTS_MAX = 8;    // parts of its down projection along K
+
 struct Plan { bool stream; int ksplit; int tile_rows; bool do_gateup; bool do_down; };
 Plan make_plan(int mean_rows, int n_experts_layer, int policy_word) {
   Plan p{};
@@ -35,12 +39,23 @@ Plan make_plan(int mean_rows, int n_experts_layer, int policy_word) {
     case 4: p.stream = false; p.tile_rows = 256; return p;
     case 5: p.stream = false; p.tile_rows = 129; return p;
     case 8: p.stream = false; p.tile_rows = 64; return p;
+    case 9: p.stream = true; p.ksplit = 9; return p;
     default: break;
   }
   const bool few_experts = n_experts_layer < 16;   // e.g. the shared expert: one weight set, all rows
-  if (mean_rows <= (few_experts ? 128 : 48)) {
+  if (few_experts) {
+    // measured with cold caches at the Qwen shape: K-split streaming wins up to 16 rows, the
+    // 128x64 tiles with a K-cut down projection up to 512 rows, the large tiles beyond
+    if (mean_rows <= 16) { p.stream = true; p.ksplit = 4; }
+    else if (mean_rows <= SHARED_SMALL_T) { p.stream = false; p.tile_rows = 64; }
+    else { p.stream = false; p.tile_rows = 0; }
+    return p;
+  }
+  // routed experts, measured with cold caches at the Qwen shape: streaming through LDS rings wins
+  // up to a mean of about 26 rows per expert (T = 384), the MFMA tiles beyond
+  if (mean_rows <= 26) {
     p.stream = true;
-    p.ksplit = few_experts ? 4 : 1;   // few experts: split K over the waves to get enough of them
+    p.ksplit = 9;
   } else {
     p.stream = false;
     p.tile_rows = 0;   // 256- or 128-row tiles, picked per kernel from the tile count
@@ -50,6 +65,11 @@ Plan make_plan(int mean_rows, int n_experts_layer, int policy_word) {
 
 int ffn_forward(const GemmArgs& gu, const GemmArgs& dn, const Plan& p, hipStream_t st) {
   int rc = 0;
+  if (p.stream && p.ksplit == 9) {
+    if (p.do_gateup && (rc = launch_stream_lds_gateup(gu, st)) != 0) return rc;
+    if (p.do_down) rc = launch_stream_lds_down(dn, st);
+    return rc;
+  }
   if (p.stream) {
     if (p.do_gateup && (rc = launch_stream_gateup(gu, p.ksplit, st)) != 0) return rc;
     if (p.do_down) rc = launch_stream_down(dn, p.ksplit, st);
@@ -85,8 +105,6 @@ size_t moe_expert_workspace_bytes(int P, int I) {
   return align256((size_t)P * (size_t)I * 2);
 }
 // h [T,Is] bf16, then (small batches only) the fp32 partial outputs of a down projection cut along K
-constexpr int SHARED_SMALL_T = 256;
-constexpr int SHARED_KPARTS_MAX = 8;
 size_t moe_shared_workspace_bytes(int T, int H, int Is) {
   if (T <= 0 || H <= 0 || Is <= 0) return 0;
   size_t n = align256((size_t)T * (size_t)Is * 2);

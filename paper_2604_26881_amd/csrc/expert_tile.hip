@@ -61,20 +61,6 @@ struct TileShape {
 
 constexpr int TILE_EMAX = 256;
 
-// One 16-byte-per-lane copy from global memory straight into LDS (no registers in between):
-// lane l of the wave writes LDS bytes [lds + 16*l, +16) from global address base + voff.
-// The copy is asynchronous; it is counted by vmcnt like any other vector memory load.
-__device__ __forceinline__ void copy_to_lds_16(const void* base, uint32_t voff, uint32_t lds) {
-  asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(base), "s"(lds)
-               : "memory", "m0");
-}
-template <int N>
-__device__ __forceinline__ void wait_copies_but() {   // all but the N most recent copies have landed
-  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
-}
-__device__ __forceinline__ void workgroup_barrier() { asm volatile("s_barrier" ::: "memory"); }
-__device__ __forceinline__ void wait_lds_reads() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
-
 template <int BM, int BN, int WAVES_M, int WAVES_N, bool GATEUP, int NS, int OCC, int KSPLIT>
 __global__ __launch_bounds__(256, OCC) void expert_tile_kernel(GemmArgs a) {
   using S = TileShape<BM, BN, WAVES_M, WAVES_N, GATEUP, NS>;

@@ -178,7 +178,7 @@ def skewed_workload(T, H, E, K, I, Is, seed):
     return workloads.prefill(seed=seed, T=T, H=H, E=E, K=K, I=I, Is=Is)
 
 
-@pytest.mark.parametrize("policy", [0, 1, 2, 3, 4, 5, 6, 7])
+@pytest.mark.parametrize("policy", [0, 1, 2, 3, 4, 5, 6, 7, 8, 9])
 def test_expert_blocks_match_oracle(moe, oracle64, policy):
     wl = skewed_workload(T=700, H=256, E=20, K=4, I=192, Is=0, seed=21)
     s = wl.shape
@@ -209,7 +209,7 @@ def test_expert_blocks_match_oracle(moe, oracle64, policy):
     check_close(f64(out), ref["out"], f"layer output policy {policy}")
 
 
-@pytest.mark.parametrize("policy", [0, 1, 2, 3, 4, 5, 6, 7, 8])
+@pytest.mark.parametrize("policy", [0, 1, 2, 3, 4, 5, 6, 7, 8, 9])
 @pytest.mark.parametrize("T", [5, 130, 300])
 def test_shared_expert_matches_oracle(moe, oracle64, policy, T):
     wl = workloads.decode(seed=31, T=T, H=256, E=8, I=64, Is=448)
