@@ -57,7 +57,8 @@ def main() -> int:
     ap.add_argument("--no-graph", action="store_true")
     ap.add_argument("--overlap-shared", type=int, default=-1,
                     help="1: shared expert on a second stream, concurrent with the routed path; 0: one stream; "
-                         "-1: on for the decode workload (bandwidth-bound kernels that leave CUs free)")
+                         "-1 (default): on (the shared expert depends on x only, so it fills the gaps "
+                         "the routing, permute and tail phases of the routed path leave)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     args = ap.parse_args()
@@ -103,7 +104,7 @@ def main() -> int:
     # phase bits of the *_ex policy word: 0x100 = gate/up kernel only, 0x200 = down kernel only
     GU, DN = 0x100, 0x200
     names = ["routed_gateup", "routed_down", "shared_gateup", "shared_down"]
-    overlap = (args.workload == "decode") if args.overlap_shared < 0 else bool(args.overlap_shared)
+    overlap = True if args.overlap_shared < 0 else bool(args.overlap_shared)
     overlap = overlap and shared is not None
     side_stream = torch.cuda.Stream() if overlap else None
     block_streams = [torch.cuda.Stream() for _ in range(args.block_streams)] if args.block_streams > 1 else []

@@ -386,7 +386,7 @@ static int launch_tile_t(const GemmArgs& a, hipStream_t st) {
 static int pick_tile_rows(const GemmArgs& a, int tile_rows, int nout, bool down) {
   if (tile_rows != 0) return tile_rows;
   if (a.offsets != nullptr)   // experts of mixed sizes (measured on Zipf-skewed routing)
-    return (down && a.mean_rows >= 128) ? 256 : 129;
+    return (down && a.mean_rows >= 200) ? 256 : 129;
   const long tiles256 = (((long)a.rows_total + 255) / 256) * ((a.N + nout - 1) / nout);
   return tiles256 >= (long)num_cus() ? 256 : 129;
 }
