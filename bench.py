@@ -11,12 +11,13 @@ all through the C ABI.  Prints ONE JSON line.
 The timed region runs the K steps twice: once eagerly with HIP events around each grouped-GEMM
 launch (these give the per-kernel durations the roofline figures use; one stream, one kernel at a
 time), and once as replays of a HIP graph of the same step (no host launch cost between kernels;
-for the decode workload the shared expert runs on a second stream inside the graph).  `value` comes from the graph
+the shared expert runs on a second stream inside the graph unless --overlap-shared 0).  `value` comes from the graph
 replays unless --no-graph is given; both step times are in the JSON line.
 """
 from __future__ import annotations
 
 import argparse
+import hashlib
 import json
 import os
 import sys
@@ -42,6 +43,31 @@ def layer_flops_per_token(s) -> int:
     return routed + shared + router + gate
 
 
+def csrc_sha256() -> str:
+    """Hash of the kernel sources: stored profiler counters are only valid for the kernels they were taken on."""
+    root = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2604_26881_amd", "csrc")
+    h = hashlib.sha256()
+    for name in sorted(os.listdir(root)):
+        with open(os.path.join(root, name), "rb") as f:
+            h.update(name.encode() + b"\0" + f.read())
+    return h.hexdigest()
+
+
+def measured_traffic(args, kernel: str):
+    """HBM bytes per launch of `kernel` from stored rocprofv3 counter runs (FETCH_SIZE and WRITE_SIZE, each
+    scaled by the same counter's reading for a plain copy of known size), or None when there is no
+    such record for this workload and launch configuration, or the kernel sources have changed since."""
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "hbm_traffic.json")
+    if args.policy != 0 or args.shared_policy != 0 or args.group_size != 0 or not os.path.exists(path):
+        return None
+    with open(path) as f:
+        rec = json.load(f)
+    if rec.get("csrc_sha256") != csrc_sha256():
+        return None
+    e = rec.get("entries", {}).get(f"{args.workload}:{kernel}")
+    return None if e is None else e["hbm_bytes_per_launch"]
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -59,6 +85,9 @@ def main() -> int:
                     help="1: shared expert on a second stream, concurrent with the routed path; 0: one stream; "
                          "-1 (default): on (the shared expert depends on x only, so it fills the gaps "
                          "the routing, permute and tail phases of the routed path leave)")
+    ap.add_argument("--calibration-copy-mib", type=int, default=0,
+                    help="before the timed steps, run three plain device copies of this many MiB (a kernel of "
+                         "known HBM traffic, to scale profiler byte counters taken in the same run)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     args = ap.parse_args()
@@ -172,6 +201,13 @@ def main() -> int:
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    if args.calibration_copy_mib > 0:
+        src = torch.ones(args.calibration_copy_mib << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- timed region 1: eager, events around the four grouped-GEMM launches
     events = []
@@ -239,6 +275,7 @@ def main() -> int:
         achieved = alg_flops[dom] / launches / dur_s / 1e12
         roof = {"bound": "mfma", "achieved": achieved, "peak": PEAK_MFMA_BF16_TFLOPS, "unit": "TFLOP/s",
                 "frac": achieved / PEAK_MFMA_BF16_TFLOPS, "traffic": None}
+    roof["traffic"] = measured_traffic(args, dom)
     roof.update({"kernel": dom, "launch_us": dur_s * 1e6, "launches_per_step": launches,
                  "algorithmic_flops_per_launch": alg_flops[dom] / launches,
                  "algorithmic_bytes_per_launch": alg_bytes[dom] / launches})
@@ -264,7 +301,7 @@ def main() -> int:
         "ms_per_step_eager": eager_ms, "ms_per_step_graph": graph_ms,
         "layer_tflops": layer_tflops, "layer_frac_of_mfma_peak": layer_tflops / PEAK_MFMA_BF16_TFLOPS,
         "layer_gbs": layer_bytes / (ms * 1e-3) / 1e9, "layer_frac_of_hbm_peak": layer_bytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
-        "flop_per_token": flop_tok, "roofline": roof, "kernels": kernels,
+        "flop_per_token": flop_tok, "roofline": roof, "kernels": kernels, "csrc_sha256": csrc_sha256(),
     }
 
     # ---- CPU baseline: the oracle, per-token definition, on a bounded sample of the same batch

@@ -1,10 +1,10 @@
 // Gating kernel: router logits, softmax and top-k per token (FaaSMoE Sec. 2.1: the gating
 // network selects the top-k experts for each token; Sec. 3: it runs in the orchestrator).
 //
-// One workgroup of four waves serves TOK tokens.  The experts are dealt to the four waves EB at a
-// time; a wave keeps the TOK token rows in registers as fp32, streams EB router rows per step and
-// forms TOK*EB dot products at once (independent accumulator chains) in the fixed order of the
-// interface: lane j owns elements 512*c + 8*j .. +7 of every 512-element chunk c (one 16-byte
+// A wave keeps TOK token rows in registers as fp32, streams EB router rows per step and forms
+// TOK*EB dot products at once; the waves of a workgroup either share the tokens and split the
+// experts, or each take their own tokens and all the experts.  The dot products are formed
+// (independent accumulator chains) in the fixed order of the interface: lane j owns elements 512*c + 8*j .. +7 of every 512-element chunk c (one 16-byte
 // load per chunk) and accumulates them in ascending index by fused multiply-add; the 64 lane sums
 // are folded pairwise over lane strides 1, 2, 4, 8, 16, 32.  The fold runs on the VALU with DPP
 // lane selects: after the stride-1 and stride-2 steps the four lanes of a quad hold the same
@@ -49,13 +49,18 @@ __device__ __forceinline__ void widen8(u32x4 v, float* f) {
   f[4] = bf16_lo(v.z); f[5] = bf16_hi(v.z); f[6] = bf16_lo(v.w); f[7] = bf16_hi(v.w);
 }
 
-template <int C, int TOK, int EB, int NW>
+template <int C, int TOK, int EB, int NW, bool TSPLIT>
 __global__ __launch_bounds__(NW * 64) void route_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ Wr,
                                                         const float* __restrict__ bias, int T, int H, int E, int K,
                                                         int renorm, int32_t* __restrict__ ids, float* __restrict__ w) {
-  __shared__ float s_logit[TOK][ROUTE_EMAX];
+  constexpr int WTOK = TSPLIT ? NW * TOK : TOK;   // tokens of the workgroup
+  __shared__ float s_logit[WTOK][ROUTE_EMAX];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int t0 = blockIdx.x * TOK;
+  // TSPLIT: every wave has its own TOK tokens and walks all experts (the waves read the same router
+  // rows at about the same time, so they reach L2 once per workgroup); otherwise the waves share
+  // TOK tokens and split the experts.
+  const int t0 = blockIdx.x * WTOK + (TSPLIT ? wave * TOK : 0);
+  const int lrow = TSPLIT ? wave * TOK : 0;        // first row of this wave in s_logit
 
   // token rows -> fp32 registers (zero beyond H or T; a zero product leaves a partial sum unchanged)
   float xf[TOK][C][8];
@@ -110,15 +115,15 @@ __global__ __launch_bounds__(NW * 64) void route_kernel(const bf16_t* __restrict
         for (int tk = 0; tk < TOK; ++tk) {
           float r = fold_sum(a[i][tk]);
           if (bias) r = r + b;
-          if (lane == 0) s_logit[tk][e] = r;
+          if (lane == 0) s_logit[lrow + tk][e] = r;
         }
       }
     }
   };
   {
-    constexpr int STEP = NW * EB;
+    constexpr int STEP = TSPLIT ? EB : NW * EB;
     u32x4 wrA[EB][C], wrB[EB][C];
-    int e0 = wave * EB;
+    int e0 = TSPLIT ? 0 : wave * EB;
     if (e0 < E) load_batch(wrA, e0);
     while (e0 < E) {
       const int e1 = e0 + STEP, e2 = e0 + 2 * STEP;
@@ -133,8 +138,9 @@ __global__ __launch_bounds__(NW * 64) void route_kernel(const bf16_t* __restrict
   }
   __syncthreads();
 
-  for (int tk = wave; tk < TOK; tk += NW) {
-    const int t = t0 + tk;
+  const int tbase = blockIdx.x * WTOK;
+  for (int tk = wave; tk < WTOK; tk += NW) {
+    const int t = tbase + tk;
     if (t >= T) break;
     float l[4];
     bool taken[4];
@@ -181,26 +187,29 @@ __global__ __launch_bounds__(NW * 64) void route_kernel(const bf16_t* __restrict
   }
 }
 
-template <int C, int TOK, int EB, int NW>
+template <int C, int TOK, int EB, int NW, bool TSPLIT = false>
 static int launch_route_t(const void* x, const void* Wr, const float* bias, int T, int H, int E, int K, int renorm,
                           int32_t* ids, float* w, hipStream_t st) {
-  const int blocks = (T + TOK - 1) / TOK;
-  hipLaunchKernelGGL((route_kernel<C, TOK, EB, NW>), dim3(blocks), dim3(NW * 64), 0, st, (const bf16_t*)x,
+  constexpr int WTOK = TSPLIT ? NW * TOK : TOK;
+  const int blocks = (T + WTOK - 1) / WTOK;
+  hipLaunchKernelGGL((route_kernel<C, TOK, EB, NW, TSPLIT>), dim3(blocks), dim3(NW * 64), 0, st, (const bf16_t*)x,
                      (const bf16_t*)Wr, bias, T, H, E, K, renorm, ids, w);
   return hipGetLastError() == hipSuccess ? 0 : -4;
 }
 
-// Few tokens: one token per workgroup of 8 waves, each wave takes its experts in one batch (latency).
-// Many tokens: two tokens per workgroup of 4 waves, batches of 4 experts (throughput).
+// Few tokens: one token per workgroup of 8 waves that split the experts, each wave takes its
+// experts in one batch (latency).  Many tokens: 4 waves with two tokens each, every wave walks all
+// experts in batches of 4 (throughput; measured 53 against 61 us at T = 4096 for the same waves
+// splitting the experts of two shared tokens).
 #define MOE_ROUTE_ARGS x, Wr, bias, T, H, E, K, renorm, ids, w, st
 int launch_route(const void* x, const void* Wr, const float* bias, int T, int H, int E, int K, int renorm,
                  int32_t* ids, float* w, hipStream_t st) {
   const int chunks = (H + 511) / 512;
   const bool many = T >= 1024;
-  if (chunks <= 1) return many ? launch_route_t<1, 4, 4, 4>(MOE_ROUTE_ARGS) : launch_route_t<1, 1, 8, 8>(MOE_ROUTE_ARGS);
-  if (chunks <= 2) return many ? launch_route_t<2, 2, 4, 4>(MOE_ROUTE_ARGS) : launch_route_t<2, 1, 8, 8>(MOE_ROUTE_ARGS);
-  if (chunks <= 4) return many ? launch_route_t<4, 2, 4, 4>(MOE_ROUTE_ARGS) : launch_route_t<4, 1, 4, 8>(MOE_ROUTE_ARGS);
-  if (chunks <= 8) return many ? launch_route_t<8, 2, 2, 4>(MOE_ROUTE_ARGS) : launch_route_t<8, 1, 2, 8>(MOE_ROUTE_ARGS);
+  if (chunks <= 1) return many ? launch_route_t<1, 4, 4, 4, true>(MOE_ROUTE_ARGS) : launch_route_t<1, 1, 8, 8>(MOE_ROUTE_ARGS);
+  if (chunks <= 2) return many ? launch_route_t<2, 2, 4, 4, true>(MOE_ROUTE_ARGS) : launch_route_t<2, 1, 8, 8>(MOE_ROUTE_ARGS);
+  if (chunks <= 4) return many ? launch_route_t<4, 2, 4, 4, true>(MOE_ROUTE_ARGS) : launch_route_t<4, 1, 4, 8>(MOE_ROUTE_ARGS);
+  if (chunks <= 8) return many ? launch_route_t<8, 2, 2, 4, true>(MOE_ROUTE_ARGS) : launch_route_t<8, 1, 2, 8>(MOE_ROUTE_ARGS);
   if (chunks <= 16) return launch_route_t<16, 1, 1, 4>(MOE_ROUTE_ARGS);
   return -2;
 }
