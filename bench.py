@@ -80,6 +80,9 @@ def main() -> int:
     ap.add_argument("--shared-policy", type=int, default=0)
     ap.add_argument("--block-streams", type=int, default=1,
                     help="issue the expert-block calls round-robin over this many streams (blocks are independent)")
+    ap.add_argument("--fused-gather", type=int, default=1,
+                    help="1 (default): no permuted copy of the tokens, the block calls read x through src_of_row; "
+                         "0: moe_permute writes Xp and the block calls read it")
     ap.add_argument("--no-graph", action="store_true")
     ap.add_argument("--overlap-shared", type=int, default=-1,
                     help="1: shared expert on a second stream, concurrent with the routed path; 0: one stream; "
@@ -138,20 +141,28 @@ def main() -> int:
     side_stream = torch.cuda.Stream() if overlap else None
     block_streams = [torch.cuda.Stream() for _ in range(args.block_streams)] if args.block_streams > 1 else []
 
-    def run_blocks(w, policy):
-        """One moe_expert_group_forward per block; with several streams the independent blocks overlap."""
+    fused = bool(args.fused_gather)
+
+    def block_call(x, w, lo, hi, policy):
+        if fused:
+            moe.moe_expert_group_forward_gather(lo, hi, x, buf.src_of_row, s.K, buf.expert_offsets, w["Wg"], w["Wu"],
+                                                w["Wd"], buf.Yp, buf.workspace, policy)
+        else:
+            moe.moe_expert_group_forward(lo, hi, buf.Xp, buf.expert_offsets, w["Wg"], w["Wu"], w["Wd"], buf.Yp,
+                                         buf.workspace, policy)
+
+    def run_blocks(x, w, policy):
+        """One block invocation per expert block; with several streams the independent blocks overlap."""
         if not block_streams:
             for lo, hi in groups:
-                moe.moe_expert_group_forward(lo, hi, buf.Xp, buf.expert_offsets, w["Wg"], w["Wu"], w["Wd"], buf.Yp,
-                                             buf.workspace, policy)
+                block_call(x, w, lo, hi, policy)
             return
         main = torch.cuda.current_stream()
         for st in block_streams:
             st.wait_stream(main)
         for i, (lo, hi) in enumerate(groups):
             with torch.cuda.stream(block_streams[i % len(block_streams)]):
-                moe.moe_expert_group_forward(lo, hi, buf.Xp, buf.expert_offsets, w["Wg"], w["Wu"], w["Wd"], buf.Yp,
-                                             buf.workspace, policy)
+                block_call(x, w, lo, hi, policy)
         for st in block_streams:
             main.wait_stream(st)
 
@@ -164,9 +175,9 @@ def main() -> int:
                 moe.moe_shared_forward(x, *sh, buf.S, buf.sg, buf.workspace_shared, args.shared_policy)
         route(x, w)
         moe.moe_permute(buf.topk_ids, x, s.E, buf.expert_offsets, buf.src_of_row, buf.row_of_pair, buf.Xp,
-                        buf.workspace_permute)
+                        buf.workspace_permute, materialize=not fused)
         if events is None:
-            run_blocks(w, args.policy)
+            run_blocks(x, w, args.policy)
             if sh is not None and not overlap:
                 moe.moe_shared_forward(x, *sh, buf.S, buf.sg, buf.workspace_shared, args.shared_policy)
             if overlap:
@@ -175,10 +186,10 @@ def main() -> int:
             # same kernels, launched one per call so that events can bracket each of them
             ev = [[torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)] for _ in names]
             ev[0][0].record()
-            run_blocks(w, args.policy | GU)
+            run_blocks(x, w, args.policy | GU)
             ev[0][1].record()
             ev[1][0].record()
-            run_blocks(w, args.policy | DN)
+            run_blocks(x, w, args.policy | DN)
             ev[1][1].record()
             if sh is not None:
                 ev[2][0].record()
@@ -295,6 +306,7 @@ def main() -> int:
                    "policy": args.policy, "shared_policy": args.shared_policy,
                    "launch": "hip graph replay" if graph_ms is not None else "eager",
                    "block_streams": max(1, args.block_streams),
+                   "token_gather": "inside the gate/up kernel (no permuted copy)" if fused else "permuted copy Xp",
                    "shared_expert_stream": "second stream, concurrent with the routed path" if overlap else "same stream",
                    "active_experts": active, "rows_per_expert_max": int(counts.max()),
                    "rows_per_expert_median": float(np.median(counts))},

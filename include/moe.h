@@ -75,6 +75,9 @@ int moe_route(const void* x, const void* Wr, const float* bias, int T, int H, in
  * expert_offsets[lo] .. expert_offsets[hi]-1 of Xp.
  *   topk_ids [T,K] int32 with values in [0,E) (values outside are not detected);
  *   x [T,H] bf16; expert_offsets [E+1]; src_of_row [P]; row_of_pair [P]; Xp [P,H] bf16.
+ * Xp may be NULL: then only the three index arrays are written (x is not read and may be NULL
+ * too), for callers that hand the block invocations x and src_of_row instead of a permuted copy
+ * (moe_expert_group_forward_gather).
  * workspace: moe_permute_workspace_bytes(T, K, E) bytes of scratch (pairs of each expert per chunk of
  * 64 pairs); contents are meaningless after the call.
  */
@@ -164,6 +167,20 @@ int moe_expert_group_forward_ex(int group_lo, int group_hi, const void* Xp,
 int moe_shared_forward_ex(const void* x, const void* Wsg, const void* Wsu, const void* Wsd,
                           const void* wgate, int T, int H, int Is, void* S, float* sg,
                           void* workspace, size_t workspace_bytes, int policy, void* stream);
+
+/*
+ * The same invocation without a permuted copy of the tokens: row r of the block's batch is read
+ * as x[src_of_row[r] / K, :] while the first kernel stages it (the gather of the micro-batch
+ * construction, folded into the consumer).  Same result, bit for bit, as
+ * moe_expert_group_forward_ex on Xp.  policy as for moe_expert_group_forward_ex (0 = automatic).
+ *   x [T,H] bf16 with T = P / K; src_of_row [P] int32 on the device, values in [0,P).
+ */
+int moe_expert_group_forward_gather(int group_lo, int group_hi, const void* x,
+                                    const int32_t* src_of_row, int K,
+                                    const int32_t* expert_offsets, const void* Wg, const void* Wu,
+                                    const void* Wd, int P, int H, int E, int I, void* Yp,
+                                    void* workspace, size_t workspace_bytes, int policy,
+                                    void* stream);
 
 /* Workspace sizes in bytes (multiples of 256). */
 size_t moe_permute_workspace_bytes(int T, int K, int E);

@@ -5,10 +5,12 @@ The compute lives in ``libmoe_hip.so`` (hand-written HIP kernels behind the C AB
 memory and the current stream) into those calls.  There is no CPU or PyTorch fallback: if the
 library is missing or no GPU is present, the calls raise.
 """
-from .binding import (MoeError, lib_path, load, moe_combine, moe_expert_group_forward, moe_layer_forward,
+from .binding import (MoeError, lib_path, load, moe_combine, moe_expert_group_forward, moe_expert_group_forward_gather,
+                      moe_layer_forward,
                       moe_permute, moe_residual_norm, moe_route, moe_shared_forward, moe_stack_forward,
                       moe_workspace_bytes, LayerBuffers)
 
 __all__ = ["MoeError", "lib_path", "load", "moe_route", "moe_permute", "moe_expert_group_forward",
+           "moe_expert_group_forward_gather",
            "moe_shared_forward", "moe_combine", "moe_workspace_bytes", "moe_layer_forward", "LayerBuffers",
            "moe_residual_norm", "moe_stack_forward"]

@@ -17,7 +17,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB = None
 
 SYMBOLS = ["moe_status_string", "moe_route", "moe_permute", "moe_expert_group_forward",
-           "moe_expert_group_forward_ex", "moe_shared_forward", "moe_shared_forward_ex", "moe_combine",
+           "moe_expert_group_forward_ex", "moe_expert_group_forward_gather", "moe_shared_forward", "moe_shared_forward_ex", "moe_combine",
            "moe_permute_workspace_bytes", "moe_expert_workspace_bytes", "moe_shared_workspace_bytes",
            "moe_workspace_bytes", "moe_residual_norm"]
 
@@ -52,6 +52,9 @@ def load() -> ctypes.CDLL:
     lib.moe_expert_group_forward_ex.restype = c_int
     lib.moe_expert_group_forward_ex.argtypes = [c_int, c_int, c_vp, c_vp, c_vp, c_vp, c_vp, c_int, c_int, c_int,
                                                 c_int, c_vp, c_vp, c_sz, c_int, c_vp]
+    lib.moe_expert_group_forward_gather.restype = c_int
+    lib.moe_expert_group_forward_gather.argtypes = [c_int, c_int, c_vp, c_vp, c_int, c_vp, c_vp, c_vp, c_vp, c_int,
+                                                    c_int, c_int, c_int, c_vp, c_vp, c_sz, c_int, c_vp]
     lib.moe_shared_forward.restype = c_int
     lib.moe_shared_forward.argtypes = [c_vp, c_vp, c_vp, c_vp, c_vp, c_int, c_int, c_int, c_vp, c_vp, c_vp, c_sz, c_vp]
     lib.moe_shared_forward_ex.restype = c_int
@@ -112,7 +115,9 @@ def moe_route(x, Wr, bias, K: int, renorm: bool, topk_ids=None, topk_w=None):
 
 
 def moe_permute(topk_ids, x, E: int, expert_offsets=None, src_of_row=None, row_of_pair=None, Xp=None,
-                workspace=None):
+                workspace=None, materialize: bool = True):
+    """materialize=False: only the index arrays are built (Xp is returned as None); the block calls
+    then take x and src_of_row (moe_expert_group_forward_gather)."""
     T, K = topk_ids.shape
     H = x.shape[1]
     dev = x.device
@@ -122,7 +127,9 @@ def moe_permute(topk_ids, x, E: int, expert_offsets=None, src_of_row=None, row_o
         src_of_row = torch.empty(T * K, dtype=torch.int32, device=dev)
     if row_of_pair is None:
         row_of_pair = torch.empty(T * K, dtype=torch.int32, device=dev)
-    if Xp is None:
+    if not materialize:
+        Xp = None
+    elif Xp is None:
         Xp = torch.empty((T * K, H), dtype=torch.bfloat16, device=dev)
     if workspace is None:
         workspace = torch.empty(max(int(load().moe_permute_workspace_bytes(T, K, E)), 256), dtype=torch.uint8,
@@ -149,6 +156,26 @@ def moe_expert_group_forward(group_lo: int, group_hi: int, Xp, expert_offsets, W
                                             0 if workspace is None else workspace.numel() * workspace.element_size(),
                                             int(policy), _stream())
     _check(rc, "moe_expert_group_forward")
+    return Yp
+
+
+def moe_expert_group_forward_gather(group_lo: int, group_hi: int, x, src_of_row, K: int, expert_offsets, Wg, Wu, Wd,
+                                    Yp, workspace, policy: int = 0):
+    """The block invocation reading its rows as x[src_of_row[r] // K] (no permuted copy)."""
+    P = src_of_row.shape[0]
+    H = x.shape[1]
+    E, I, _ = Wg.shape
+    if x.shape[0] * K != P:
+        raise MoeError("moe_expert_group_forward_gather: x must have P / K rows")
+    rc = load().moe_expert_group_forward_gather(int(group_lo), int(group_hi), _ptr(x, torch.bfloat16, "x"),
+                                                _ptr(src_of_row, torch.int32, "src_of_row"), int(K),
+                                                _ptr(expert_offsets, torch.int32, "expert_offsets"),
+                                                _ptr(Wg, torch.bfloat16, "Wg"), _ptr(Wu, torch.bfloat16, "Wu"),
+                                                _ptr(Wd, torch.bfloat16, "Wd"), P, H, E, I,
+                                                _ptr(Yp, torch.bfloat16, "Yp"), _ptr(workspace, None, "workspace"),
+                                                0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                                int(policy), _stream())
+    _check(rc, "moe_expert_group_forward_gather")
     return Yp
 
 
@@ -227,14 +254,16 @@ class LayerBuffers:
 def moe_layer_forward(x, Wr, bias, Wg, Wu, Wd, shared, K: int, renorm: bool,
                       groups: Optional[Sequence[Tuple[int, int]]] = None, buf: Optional[LayerBuffers] = None,
                       tenant_rows: Optional[List[Tuple[int, int]]] = None, policy: int = 0,
-                      shared_policy: int = 0, shared_stream: Optional[torch.cuda.Stream] = None) -> LayerBuffers:
+                      shared_policy: int = 0, shared_stream: Optional[torch.cuda.Stream] = None,
+                      fused_gather: bool = False) -> LayerBuffers:
     """One MoE layer in the paper's order: gating, micro-batch construction, one call per expert
     block, shared expert, aggregation.  Sequencing only; every step is a library call.
 
     shared: (Wsg, Wsu, Wsd, wgate) or None.  groups: expert blocks (lo, hi), default one block.
     tenant_rows with a [n_tenants, E] bias: gating is called once per tenant slice.
     shared_stream: run the shared expert on this stream, concurrently with gating, permutation and
-    the routed blocks (it depends on x only); the aggregation waits for it."""
+    the routed blocks (it depends on x only); the aggregation waits for it.
+    fused_gather: no permuted copy Xp; the block calls read x through src_of_row."""
     T, H = x.shape
     E, I, _ = Wg.shape
     Is = 0 if shared is None else shared[0].shape[0]
@@ -252,9 +281,13 @@ def moe_layer_forward(x, Wr, bias, Wg, Wu, Wd, shared, K: int, renorm: bool,
     else:
         moe_route(x, Wr, bias, K, renorm, buf.topk_ids, buf.topk_w)
     moe_permute(buf.topk_ids, x, E, buf.expert_offsets, buf.src_of_row, buf.row_of_pair, buf.Xp,
-                buf.workspace_permute)
+                buf.workspace_permute, materialize=not fused_gather)
     for lo, hi in (groups or [(0, E)]):
-        moe_expert_group_forward(lo, hi, buf.Xp, buf.expert_offsets, Wg, Wu, Wd, buf.Yp, buf.workspace, policy)
+        if fused_gather:
+            moe_expert_group_forward_gather(lo, hi, x, buf.src_of_row, K, buf.expert_offsets, Wg, Wu, Wd, buf.Yp,
+                                            buf.workspace, policy)
+        else:
+            moe_expert_group_forward(lo, hi, buf.Xp, buf.expert_offsets, Wg, Wu, Wd, buf.Yp, buf.workspace, policy)
     if shared is not None and shared_stream is None:
         moe_shared_forward(x, shared[0], shared[1], shared[2], shared[3], buf.S, buf.sg, buf.workspace_shared,
                            shared_policy)

@@ -80,6 +80,28 @@ int ffn_forward(const GemmArgs& gu, const GemmArgs& dn, const Plan& p, hipStream
   return rc;
 }
 
+int expert_group_forward_impl(int group_lo, int group_hi, const void* A, const int32_t* gather, int gather_div,
+                              const int32_t* expert_offsets, const void* Wg, const void* Wu, const void* Wd, int P,
+                              int H, int E, int I, void* Yp, void* workspace, size_t workspace_bytes, int policy,
+                              void* stream) {
+  if (P < 0 || !dims_ok(H) || !dims_ok(I) || E < 1 || E > 256) return MOE_ERR_SHAPE;
+  if (group_lo < 0 || group_hi > E || group_lo >= group_hi) return MOE_ERR_SHAPE;
+  if ((long long)P * (H > I ? H : I) >= (1ll << 31)) return MOE_ERR_SHAPE;
+  if (P == 0) return MOE_OK;
+  if (!A || !expert_offsets || !Wg || !Wu || !Wd || !Yp || !workspace) return MOE_ERR_NULL;
+  if (workspace_bytes < (size_t)P * (size_t)I * 2) return MOE_ERR_WORKSPACE;   // h, bf16 [P,I]
+  const int mean_rows = (P + E - 1) / E;
+  const Plan plan = make_plan(mean_rows, E, policy);
+  GemmArgs gu{};
+  gu.A = (const bf16_t*)A; gu.B0 = (const bf16_t*)Wg; gu.B1 = (const bf16_t*)Wu; gu.C = (bf16_t*)workspace;
+  gu.offsets = expert_offsets; gu.lo = group_lo; gu.hi = group_hi; gu.rows_fixed = 0; gu.rows_total = P;
+  gu.mean_rows = mean_rows; gu.N = I; gu.Kdim = H;
+  GemmArgs dn = gu;
+  gu.gather = gather; gu.gather_div = gather_div;   // only the first kernel reads token rows
+  dn.A = (const bf16_t*)workspace; dn.B0 = (const bf16_t*)Wd; dn.B1 = nullptr; dn.C = (bf16_t*)Yp;
+  dn.N = H; dn.Kdim = I;
+  return ffn_forward(gu, dn, plan, (hipStream_t)stream);
+}
 }  // namespace
 
 extern "C" {
@@ -133,7 +155,8 @@ int moe_permute(const int32_t* topk_ids, const void* x, int T, int H, int E, int
   if (T < 0 || !dims_ok(H) || E < 1 || E > 256 || K < 1 || K > 16 || K > E) return MOE_ERR_SHAPE;
   if ((long long)T * K * H >= (1ll << 31)) return MOE_ERR_SHAPE;
   if (!expert_offsets) return MOE_ERR_NULL;
-  if (T > 0 && (!topk_ids || !x || !src_of_row || !row_of_pair || !Xp || !workspace)) return MOE_ERR_NULL;
+  if (T > 0 && (!topk_ids || !src_of_row || !row_of_pair || !workspace)) return MOE_ERR_NULL;
+  if (T > 0 && Xp && !x) return MOE_ERR_NULL;   // Xp == NULL: index arrays only, x is not read
   if (T > 0 && workspace_bytes < (((size_t)T * K + 63) / 64) * (size_t)E * 4) return MOE_ERR_WORKSPACE;
   return launch_permute(topk_ids, x, T, H, E, K, expert_offsets, src_of_row, row_of_pair, Xp, workspace,
                         (hipStream_t)stream);
@@ -142,22 +165,18 @@ int moe_permute(const int32_t* topk_ids, const void* x, int T, int H, int E, int
 int moe_expert_group_forward_ex(int group_lo, int group_hi, const void* Xp, const int32_t* expert_offsets,
                                 const void* Wg, const void* Wu, const void* Wd, int P, int H, int E, int I,
                                 void* Yp, void* workspace, size_t workspace_bytes, int policy, void* stream) {
-  if (P < 0 || !dims_ok(H) || !dims_ok(I) || E < 1 || E > 256) return MOE_ERR_SHAPE;
-  if (group_lo < 0 || group_hi > E || group_lo >= group_hi) return MOE_ERR_SHAPE;
-  if ((long long)P * (H > I ? H : I) >= (1ll << 31)) return MOE_ERR_SHAPE;
-  if (P == 0) return MOE_OK;
-  if (!Xp || !expert_offsets || !Wg || !Wu || !Wd || !Yp || !workspace) return MOE_ERR_NULL;
-  if (workspace_bytes < (size_t)P * (size_t)I * 2) return MOE_ERR_WORKSPACE;   // h, bf16 [P,I]
-  const int mean_rows = (P + E - 1) / E;
-  const Plan plan = make_plan(mean_rows, E, policy);
-  GemmArgs gu{};
-  gu.A = (const bf16_t*)Xp; gu.B0 = (const bf16_t*)Wg; gu.B1 = (const bf16_t*)Wu; gu.C = (bf16_t*)workspace;
-  gu.offsets = expert_offsets; gu.lo = group_lo; gu.hi = group_hi; gu.rows_fixed = 0; gu.rows_total = P;
-  gu.mean_rows = mean_rows; gu.N = I; gu.Kdim = H;
-  GemmArgs dn = gu;
-  dn.A = (const bf16_t*)workspace; dn.B0 = (const bf16_t*)Wd; dn.B1 = nullptr; dn.C = (bf16_t*)Yp;
-  dn.N = H; dn.Kdim = I;
-  return ffn_forward(gu, dn, plan, (hipStream_t)stream);
+  return expert_group_forward_impl(group_lo, group_hi, Xp, nullptr, 1, expert_offsets, Wg, Wu, Wd, P, H, E, I, Yp,
+                                   workspace, workspace_bytes, policy, stream);
+}
+
+int moe_expert_group_forward_gather(int group_lo, int group_hi, const void* x, const int32_t* src_of_row, int K,
+                                    const int32_t* expert_offsets, const void* Wg, const void* Wu, const void* Wd,
+                                    int P, int H, int E, int I, void* Yp, void* workspace, size_t workspace_bytes,
+                                    int policy, void* stream) {
+  if (K < 1 || K > 16 || (P > 0 && P % K != 0)) return MOE_ERR_SHAPE;
+  if (P > 0 && !src_of_row) return MOE_ERR_NULL;
+  return expert_group_forward_impl(group_lo, group_hi, x, src_of_row, K, expert_offsets, Wg, Wu, Wd, P, H, E, I, Yp,
+                                   workspace, workspace_bytes, policy, stream);
 }
 
 int moe_expert_group_forward(int group_lo, int group_hi, const void* Xp, const int32_t* expert_offsets,

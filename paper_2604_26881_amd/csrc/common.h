@@ -74,6 +74,8 @@ struct GemmArgs {
   int N;               // output columns (per branch for gate/up)
   int Kdim;            // contraction length
   float* Cpart;        // fp32 partial outputs [parts, rows_total, N] of kernels that cut K, else unused
+  const int32_t* gather;   // nullptr: row r of A is A[r]; else row r of A is A[gather[r] / gather_div]
+  int gather_div;          // (the token rows themselves, addressed through src_of_row: no permuted copy)
 };
 
 int launch_route(const void* x, const void* Wr, const float* bias, int T, int H, int E, int K, int renorm,

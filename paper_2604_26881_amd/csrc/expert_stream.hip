@@ -67,8 +67,10 @@ __global__ __launch_bounds__(256) void expert_stream_kernel(GemmArgs a) {
     const int mtv = max(0, min(MT, (Me - mw + 15) / 16));
     const bf16_t* xr[MT];
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
-      xr[mt] = a.A + (size_t)(rb + min(mw + mt * 16 + r16, Me - 1)) * Kdim + 16 * kg;
+    for (int mt = 0; mt < MT; ++mt) {
+      const int r = rb + min(mw + mt * 16 + r16, Me - 1);
+      xr[mt] = a.A + (size_t)(a.gather ? a.gather[r] / a.gather_div : r) * Kdim + 16 * kg;
+    }
 
     f32x4 accg[MT], accu[MT];
 #pragma unroll

@@ -90,7 +90,8 @@ __global__ __launch_bounds__(64) void expert_stream_lds_kernel(GemmArgs a) {
 #pragma unroll
       for (int i = 0; i < 2; ++i) {
         const int m = min(m0 + mt * 16 + i * 8 + crow, Me - 1);   // rows past the end repeat the last row
-        coffX[mt][i] = (uint32_t)(rb + m) * (uint32_t)Kdim * 2u + (uint32_t)cchunk * 16u;
+        const int arow = a.gather ? a.gather[rb + m] / a.gather_div : rb + m;
+        coffX[mt][i] = (uint32_t)arow * (uint32_t)Kdim * 2u + (uint32_t)cchunk * 16u;
       }
 
     f32x4 acc0[MT], acc1[MT];

@@ -150,7 +150,8 @@ __global__ __launch_bounds__(256, OCC) void expert_tile_kernel(GemmArgs a) {
     const int eg = a.offsets ? a.lo + e : 0;
 
     const size_t kbeg = (size_t)ks * nk * S::BK;
-    const unsigned char* Ag = reinterpret_cast<const unsigned char*>(a.A + (size_t)row0 * Kdim + kbeg);
+    // with a gather list the token rows are addressed from the start of A, through the list
+    const unsigned char* Ag = reinterpret_cast<const unsigned char*>(a.A + (a.gather ? (size_t)0 : (size_t)row0 * Kdim) + kbeg);
     const unsigned char* Bg0 = reinterpret_cast<const unsigned char*>(a.B0 + (size_t)eg * a.N * Kdim + kbeg);
     const unsigned char* Bg1 = GATEUP ? reinterpret_cast<const unsigned char*>(a.B1 + (size_t)eg * a.N * Kdim + kbeg) : nullptr;
     // byte offsets of this lane's 16 bytes for each of the NL copies of a stage (K step 0)
@@ -161,6 +162,7 @@ __global__ __launch_bounds__(256, OCC) void expert_tile_kernel(GemmArgs a) {
       int grow;
       if (i < S::NLA) {
         grow = min(row, rowsValid - 1);
+        if (a.gather) grow = a.gather[row0 + grow] / a.gather_div;
       } else {
         int r = row - BM;
         if (GATEUP && i >= S::NLA + (S::NL - S::NLA) / 2) r -= BN / 2;   // second half: the up branch

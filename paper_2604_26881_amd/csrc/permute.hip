@@ -127,6 +127,7 @@ __global__ __launch_bounds__(256) void permute_scatter_kernel(const int32_t* __r
     s_row[lane] = row;
   }
   __syncthreads();
+  if (Xp == nullptr) return;   // index arrays only: the expert kernels gather the token rows themselves
   // rows of this chunk are dealt to the (split * 4) waves that serve it
   for (int i = part * 4 + wave; i < 64; i += split * 4) {
     const int row = s_row[i];
@@ -155,7 +156,7 @@ int launch_permute(const int32_t* ids, const void* x, int T, int H, int E, int K
   hipLaunchKernelGGL(permute_hist_kernel, dim3((chunks + 3) / 4), dim3(256), 0, st, ids, P, E, hist);
   if (hipGetLastError() != hipSuccess) return -4;
   // several workgroups share the row copies of one chunk, about a thousand workgroups in all
-  const int split = chunks >= 1024 ? 1 : (chunks >= 64 ? min(16, 1024 / chunks) : 16);
+  const int split = Xp == nullptr ? 1 : (chunks >= 1024 ? 1 : (chunks >= 64 ? min(16, 1024 / chunks) : 16));
   hipLaunchKernelGGL(permute_scatter_kernel, dim3(chunks * split), dim3(256), 0, st, ids, hist, (const bf16_t*)x, P,
                      E, K, H, split, offsets, src_of_row, row_of_pair, (bf16_t*)Xp);
   return hipGetLastError() == hipSuccess ? 0 : -4;

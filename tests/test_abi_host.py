@@ -72,6 +72,13 @@ def test_bad_arguments_are_rejected_before_any_launch(lib):
     assert lib.moe_expert_group_forward(0, 8, p, None, p, p, p, 32, 64, 8, 128, p, p, 1 << 20, None) == NULL
     assert lib.moe_expert_group_forward(0, 8, p, p, p, p, p, 32, 64, 8, 128, p, p, 100, None) == WS
     assert lib.moe_expert_group_forward(0, 8, None, None, None, None, None, 0, 64, 8, 128, None, None, 0, None) == 0
+    # expert block reading x through src_of_row
+    ga = lambda src, K, P: lib.moe_expert_group_forward_gather(0, 8, p, src, K, p, p, p, p, P, 64, 8, 128, p, p, 1 << 20,
+                                                               0, None)
+    assert ga(None, 2, 32) == NULL        # no gather list
+    assert ga(p, 3, 32) == SHAPE          # P is not a multiple of K
+    assert ga(p, 0, 32) == SHAPE
+    assert ga(None, 2, 0) == 0            # P = 0: no-op
     # shared expert
     assert lib.moe_shared_forward(p, p, p, p, p, 4, 64, 96, p, p, p, 1 << 20, None) == SHAPE
     assert lib.moe_shared_forward(p, p, p, p, p, 4, 64, 128, p, None, p, 1 << 20, None) == NULL

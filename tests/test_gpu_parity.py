@@ -210,6 +210,43 @@ def test_expert_blocks_match_oracle(moe, oracle64, policy):
     check_close(f64(out), ref["out"], f"layer output policy {policy}")
 
 
+@pytest.mark.parametrize("policy", [0, 1, 3, 4, 8, 9])
+def test_block_calls_reading_x_through_src_of_row_equal_the_permuted_copy(moe, oracle64, policy):
+    # every kernel family: the gather folded into the first kernel gives the same bits as the copy Xp
+    wl = skewed_workload(T=600, H=320, E=12, K=3, I=128, Is=0, seed=23)
+    s = wl.shape
+    g = wl.to("cuda")
+    ids, w = moe.moe_route(g.x, g.Wr, g.bias, s.K, s.renorm)
+    off, src, rowp, Xp = moe.moe_permute(ids, g.x, s.E)
+    off2, src2, rowp2, none = moe.moe_permute(ids, g.x, s.E, materialize=False)
+    assert none is None
+    assert torch.equal(off, off2) and torch.equal(src, src2) and torch.equal(rowp, rowp2)
+    ws = torch.empty(s.P * s.I * 2, dtype=torch.uint8, device="cuda")
+    Ya = torch.full((s.P, s.H), 768.0, dtype=torch.bfloat16, device="cuda")
+    Yb = torch.full((s.P, s.H), 768.0, dtype=torch.bfloat16, device="cuda")
+    for lo, hi in [(0, 5), (5, 12)]:
+        moe.moe_expert_group_forward(lo, hi, Xp, off, g.Wg, g.Wu, g.Wd, Ya, ws, policy)
+    for lo, hi in [(0, 5), (5, 12)]:
+        moe.moe_expert_group_forward_gather(lo, hi, g.x, src, s.K, off, g.Wg, g.Wu, g.Wd, Yb, ws, policy)
+    torch.cuda.synchronize()
+    assert torch.equal(Ya.view(torch.int16), Yb.view(torch.int16))
+    d = wl.f32_numpy()
+    ref = oracle64.layer(d["x"], d["Wr"], d["bias"], d["Wg"], d["Wu"], d["Wd"], None, s.K, s.renorm)
+    check_close(f64(Yb), ref["Yp"], f"Yp, rows gathered by the kernel, policy {policy}")
+
+
+def test_layer_with_fused_gather_at_decode_and_prefill_sizes(moe, oracle64):
+    for wl in (workloads.decode(), workloads.prefill()):     # the sizes the benchmark times
+        s = wl.shape
+        g = wl.to("cuda")
+        sh = (g.Wsg, g.Wsu, g.Wsd, g.wgate)
+        a = moe.moe_layer_forward(g.x, g.Wr, g.bias, g.Wg, g.Wu, g.Wd, sh, s.K, s.renorm)
+        b = moe.moe_layer_forward(g.x, g.Wr, g.bias, g.Wg, g.Wu, g.Wd, sh, s.K, s.renorm, fused_gather=True)
+        torch.cuda.synchronize()
+        assert torch.equal(a.out.view(torch.int16), b.out.view(torch.int16)), wl.name
+        assert torch.equal(a.Yp.view(torch.int16), b.Yp.view(torch.int16)), wl.name
+
+
 @pytest.mark.parametrize("policy", [0, 1, 2, 3, 4, 5, 6, 7, 8, 9])
 @pytest.mark.parametrize("T", [5, 130, 300])
 def test_shared_expert_matches_oracle(moe, oracle64, policy, T):
