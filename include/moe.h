@@ -153,7 +153,8 @@ int moe_residual_norm(const void* x, const void* y, int T, int H, float eps, voi
  * token rows by 64 weight rows (for the shared expert, whose workspace has room for them, the down
  * projection is cut into up to 8 parts along K whose fp32 partial sums a second kernel adds in
  * ascending order; with policy 8 and T > 512 the shared call needs the workspace of
- * moe_shared_workspace_bytes plus 8*T*H*4 bytes).
+ * moe_shared_workspace_bytes plus 8*T*H*4 bytes); 9 = weight-streaming kernels that stage the
+ * weights through wave-private LDS rings; 10 = MFMA tiles of 128 token rows by 128 weight rows.
  * Every policy computes the same function; results may differ in the last bf16 bit between
  * policies because the fp32 summation order differs.  Use one policy for all blocks of a layer.
  * Adding 0x100 to policy runs only the first kernel of the call (gate/up projections and SwiGLU

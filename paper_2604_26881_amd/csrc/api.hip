@@ -17,10 +17,11 @@ bool dims_ok(int H) { return H > 0 && H % 64 == 0; }
 //         3 and 5 = MFMA tiles of 128 rows; 4 = MFMA tiles of 256 rows; 6 = streaming, the waves split the token
 //         tiles; 7 = streaming, two-way token split times two-way K split; 8 = MFMA tiles of 128 rows
 //         by 64 weight rows, the down projection cut along K (few rows in all, one weight set);
-//         9 = streaming through wave-private LDS rings (whole-line requests).
+//         9 = streaming through wave-private LDS rings (whole-line requests); 10 = MFMA tiles of
+//         128 rows by 128 weight rows.
 // Bits 8 and 9 of the policy word restrict a call to one of its two kernels (0x100: gate/up
 // only, 0x200: down projection only), so that each can be timed on its own.
-constexpr int SHARED_SMALL_T = 512;     // up to here the shared expert runs on the 128x64 tiles
+constexpr int SHARED_SMALL_T = 512;     // up to here the workspace has room for a K-cut down projection
 constexpr int SHARED_KPARTS_MAX = 8;    // parts of its down projection along K
 
 struct Plan { bool stream; int ksplit; int tile_rows; bool do_gateup; bool do_down; };
@@ -40,14 +41,14 @@ Plan make_plan(int mean_rows, int n_experts_layer, int policy_word) {
     case 5: p.stream = false; p.tile_rows = 129; return p;
     case 8: p.stream = false; p.tile_rows = 64; return p;
     case 9: p.stream = true; p.ksplit = 9; return p;
+    case 10: p.stream = false; p.tile_rows = 130; return p;
     default: break;
   }
   const bool few_experts = n_experts_layer < 16;   // e.g. the shared expert: one weight set, all rows
   if (few_experts) {
-    // measured with cold caches at the Qwen shape: K-split streaming wins up to 16 rows, the
-    // 128x64 tiles with a K-cut down projection up to 512 rows, the large tiles beyond
+    // measured with cold caches at the Qwen shape: K-split streaming wins up to 16 rows; beyond
+    // that MFMA tiles whose shape each kernel picks from its tile count (pick_tile_shape)
     if (mean_rows <= 16) { p.stream = true; p.ksplit = 4; }
-    else if (mean_rows <= SHARED_SMALL_T) { p.stream = false; p.tile_rows = 64; }
     else { p.stream = false; p.tile_rows = 0; }
     return p;
   }
@@ -197,10 +198,16 @@ int moe_shared_forward_ex(const void* x, const void* Wsg, const void* Wsu, const
   if (workspace_bytes < (size_t)T * (size_t)Is * 2) return MOE_ERR_WORKSPACE;   // h, bf16 [T,Is]
   const Plan plan = make_plan(T, 1, policy);
   const size_t h_bytes = align256((size_t)T * (size_t)Is * 2);
+  const size_t part_bytes = (size_t)tile_down_ksplit(Is) * (size_t)T * (size_t)H * 4;
   float* part = nullptr;
-  if (!plan.stream && plan.tile_rows == 64 && tile_down_ksplit(Is) > 1) {
-    if (workspace_bytes < h_bytes + (size_t)tile_down_ksplit(Is) * (size_t)T * (size_t)H * 4) return MOE_ERR_WORKSPACE;
-    part = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + h_bytes);
+  if (!plan.stream && tile_down_ksplit(Is) > 1) {
+    if (plan.tile_rows == 64) {          // asked for by the caller: the room must be there
+      if (workspace_bytes < h_bytes + part_bytes) return MOE_ERR_WORKSPACE;
+      part = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + h_bytes);
+    } else if (plan.tile_rows == 0 && T <= SHARED_SMALL_T) {   // automatic: sizes the helper reports include it
+      if (workspace_bytes < h_bytes + part_bytes) return MOE_ERR_WORKSPACE;
+      part = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + h_bytes);
+    }
   }
   GemmArgs gu{};
   gu.A = (const bf16_t*)x; gu.B0 = (const bf16_t*)Wsg; gu.B1 = (const bf16_t*)Wsu; gu.C = (bf16_t*)workspace;

@@ -90,6 +90,7 @@ int launch_gate_dot(const void* x, const void* wgate, int T, int H, float* sg, h
 int launch_tile_gateup(const GemmArgs& a, int tile_rows, hipStream_t st);
 int launch_tile_down(const GemmArgs& a, int tile_rows, hipStream_t st);
 int tile_down_ksplit(int Kdim);   // K parts of the down projection when tile_rows == 64
+int pick_tile_shape(int rows, int N, int Kdim, bool gateup, bool allow_kcut);   // one weight set, known rows
 int launch_stream_gateup(const GemmArgs& a, int ksplit, hipStream_t st);
 int launch_stream_down(const GemmArgs& a, int ksplit, hipStream_t st);
 // Streaming kernels that stage the weights through wave-private LDS rings (whole-line requests).

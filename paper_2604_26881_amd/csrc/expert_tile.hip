@@ -381,24 +381,54 @@ static int launch_tile_t(const GemmArgs& a, hipStream_t st) {
   return 0;
 }
 
-// tile_rows: 256 or 128 (129 is accepted as 128) token rows per tile; 64 = 128 token rows by 64 weight
-// rows (few rows in all: many small tiles so that every CU streams a share of the weights; the down
-// projection is also cut along K and its parts are summed in order by a second kernel);
-// 0 = choose from layer-wide sizes only (never from the block bounds).
+// Tile shape codes: 256 = 256x256, 128/129 = 128 token rows x 256 weight rows, 130 = 128x128,
+// 64 = 128x64 (for the down projection with a K cut into parts summed in order by a second kernel
+// when the caller provides room for the partial sums); 0 = choose from layer-wide sizes only
+// (never from the block bounds).
+//
+// One weight set on a known number of rows (the shared expert): the shape with the least estimated
+// time.  A launch takes ceil(items / CUs) rounds of one tile each, a tile costs rows x columns x K
+// times a per-shape factor (smaller tiles move more bytes per flop through LDS).  The factors come
+// from timing the four shapes at T = 128 ... 8192 on the Qwen shape; the K cut pays a reduction
+// pass over its fp32 partial sums.
+int tile_down_ksplit(int Kdim) { return Kdim % 512 == 0 ? 8 : Kdim % 256 == 0 ? 4 : Kdim % 128 == 0 ? 2 : 1; }
+int pick_tile_shape(int rows, int N, int Kdim, bool gateup, bool allow_kcut) {
+  struct Cand { int code, bm, nout; double c; };
+  const Cand cands[4] = {{256, 256, gateup ? 128 : 256, 1.0}, {129, 128, gateup ? 128 : 256, 1.1},
+                         {130, 128, gateup ? 64 : 128, 1.42}, {64, 128, gateup ? 32 : 64, 1.77}};
+  const double cus = (double)num_cus();
+  const double units_per_us = 2.1e6;   // 256x256x5632 tile: about 175 us
+  int best = 129;
+  double best_cost = 0.0;
+  for (const Cand& k : cands) {
+    int parts = 1;
+    if (k.code == 64) {
+      if (!gateup && !allow_kcut) continue;   // 32 column tiles would leave most CUs idle
+      if (!gateup) parts = tile_down_ksplit(Kdim);
+    }
+    const double items = (double)((rows + k.bm - 1) / k.bm) * (double)((N + k.nout - 1) / k.nout) * parts;
+    const double rounds = (double)(long)((items + cus - 1) / cus);
+    double cost = rounds * k.bm * k.nout * ((double)Kdim / parts) * k.c;
+    if (parts > 1) cost += (4.0 + (double)rows * N * parts * 4.0 / 4.0e6) * units_per_us;
+    if (best_cost == 0.0 || cost < best_cost) { best_cost = cost; best = k.code; }
+  }
+  return best;
+}
+
 static int pick_tile_rows(const GemmArgs& a, int tile_rows, int nout, bool down) {
+  (void)nout;
   if (tile_rows != 0) return tile_rows;
   if (a.offsets != nullptr)   // experts of mixed sizes (measured on Zipf-skewed routing)
     return (down && a.mean_rows >= 200) ? 256 : 129;
-  const long tiles256 = (((long)a.rows_total + 255) / 256) * ((a.N + nout - 1) / nout);
-  return tiles256 >= (long)num_cus() ? 256 : 129;
+  return pick_tile_shape(a.rows_total, a.N, a.Kdim, !down, a.Cpart != nullptr);
 }
 int launch_tile_gateup(const GemmArgs& a, int tile_rows, hipStream_t st) {
   const int t = pick_tile_rows(a, tile_rows, 128, false);
   if (t == 64) return launch_tile_t<128, 64, 4, 1, true, 6, 1>(a, st);
+  if (t == 130) return launch_tile_t<128, 128, 2, 2, true, 4, 1>(a, st);
   if (t >= 256) return launch_tile_t<256, 256, 2, 2, true, 2, 1>(a, st);
   return launch_tile_t<128, 256, 1, 4, true, 3, 1>(a, st);
 }
-int tile_down_ksplit(int Kdim) { return Kdim % 512 == 0 ? 8 : Kdim % 256 == 0 ? 4 : Kdim % 128 == 0 ? 2 : 1; }
 int launch_tile_down(const GemmArgs& a, int tile_rows, hipStream_t st) {
   const int t = pick_tile_rows(a, tile_rows, 256, true);
   if (t == 64) {
@@ -409,6 +439,7 @@ int launch_tile_down(const GemmArgs& a, int tile_rows, hipStream_t st) {
       default: return launch_tile_t<128, 64, 4, 1, false, 6, 1, 1>(a, st);
     }
   }
+  if (t == 130) return launch_tile_t<128, 128, 2, 2, false, 4, 1>(a, st);
   if (t >= 256) return launch_tile_t<256, 256, 2, 2, false, 2, 1>(a, st);
   return launch_tile_t<128, 256, 1, 4, false, 3, 1>(a, st);
 }

@@ -179,7 +179,7 @@ def skewed_workload(T, H, E, K, I, Is, seed):
     return workloads.prefill(seed=seed, T=T, H=H, E=E, K=K, I=I, Is=Is)
 
 
-@pytest.mark.parametrize("policy", [0, 1, 2, 3, 4, 5, 6, 7, 8, 9])
+@pytest.mark.parametrize("policy", [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10])
 def test_expert_blocks_match_oracle(moe, oracle64, policy):
     wl = skewed_workload(T=700, H=256, E=20, K=4, I=192, Is=0, seed=21)
     s = wl.shape
@@ -247,7 +247,7 @@ def test_layer_with_fused_gather_at_decode_and_prefill_sizes(moe, oracle64):
         assert torch.equal(a.Yp.view(torch.int16), b.Yp.view(torch.int16)), wl.name
 
 
-@pytest.mark.parametrize("policy", [0, 1, 2, 3, 4, 5, 6, 7, 8, 9])
+@pytest.mark.parametrize("policy", [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10])
 @pytest.mark.parametrize("T", [5, 130, 300])
 def test_shared_expert_matches_oracle(moe, oracle64, policy, T):
     wl = workloads.decode(seed=31, T=T, H=256, E=8, I=64, Is=448)
@@ -281,6 +281,24 @@ def test_shared_expert_small_tiles_match_oracle(moe, oracle64, T, Is):
     if Is == 1024:   # without room for the partial sums the call is refused, nothing is launched
         with pytest.raises(moe.MoeError):
             moe.moe_shared_forward(g.x, g.Wsg, g.Wsu, g.Wsd, g.wgate, S, sg, ws[:h_bytes], 8)
+
+
+@pytest.mark.parametrize("T,H,Is", [(40, 256, 1024), (200, 256, 1024), (600, 256, 1024), (17, 512, 640), (512, 128, 2048),
+                                    (1500, 384, 768)])
+def test_shared_expert_automatic_shapes_match_oracle(moe, oracle64, T, H, Is):
+    # the library picks the tile shape (and whether the down projection is cut along K) from T, H and Is;
+    # the workspace is the size its helper reports
+    wl = workloads.decode(seed=41, T=T, H=H, E=8, I=64, Is=Is)
+    d = wl.f32_numpy()
+    S_ref, sg_ref = oracle64.shared_forward(d["x"], d["Wsg"], d["Wsu"], d["Wsd"], d["wgate"])
+    g = wl.to("cuda")
+    S = torch.full((T, H), 768.0, dtype=torch.bfloat16, device="cuda")
+    sg = torch.empty(T, dtype=torch.float32, device="cuda")
+    ws = torch.empty(int(moe.load().moe_shared_workspace_bytes(T, H, Is)), dtype=torch.uint8, device="cuda")
+    moe.moe_shared_forward(g.x, g.Wsg, g.Wsu, g.Wsd, g.wgate, S, sg, ws)
+    torch.cuda.synchronize()
+    check_close(f64(S), S_ref, f"shared expert, automatic shape, T={T} H={H} Is={Is}")
+    assert np.allclose(sg.cpu().numpy(), sg_ref, rtol=1e-4, atol=1e-5)
 
 
 def test_combine_matches_oracle(moe, oracle64):
