@@ -31,6 +31,7 @@
 // of one token row per accumulator quad, which makes the bf16 stores 8 bytes wide.
 // Rows past the end of an expert are clamped on load (they recompute the expert's last row) and
 // masked on store, which keeps the K loop free of branches.
+#include <type_traits>
 #include "common.h"
 
 namespace moe {
@@ -186,17 +187,18 @@ __global__ __launch_bounds__(256, OCC) void expert_tile_kernel(GemmArgs a) {
 #define MOE_TILE_ISSUE(kt, st)                                                                      \
     { _Pragma("unroll") for (int i = 0; i < S::NL; ++i) MOE_TILE_ISSUE1(kt, st, i); }
 
-    // fragment f of the 16-wide K slice kk_ of a stage, LDS -> registers: f < TB is the token block
-    // f, otherwise the weight block f - TB
+    // fragment f of the 16-wide K slice kk_ of a stage, LDS -> registers: f < TBc is the token block
+    // f, otherwise the weight block f - TBc.  TBc <= TB is the number of 32-row token blocks of this
+    // wave that hold rows of the expert: blocks of pure padding are neither read nor multiplied.
 #define MOE_TILE_READ1(fa_, fb_, stage_, kk_, f_)                                                   \
     {                                                                                               \
       const unsigned char* As_ = smem + (stage_) * S::STAGE;                                         \
       const int cr_ = (((kk_) * 2 + frag_half) ^ frag_swz) << 4;                                     \
-      if ((f_) < S::TB) {                                                                           \
-        fa_[(f_) < S::TB ? (f_) : 0] = as_bf16x8(*reinterpret_cast<const u32x4*>(                    \
+      if ((f_) < TBc) {                                                                             \
+        fa_[(f_) < TBc ? (f_) : 0] = as_bf16x8(*reinterpret_cast<const u32x4*>(                    \
             As_ + (wm * S::WTM + (f_) * 32 + frag_row) * S::ROWB + cr_));                            \
       } else {                                                                                      \
-        const int nb_ = (f_) < S::TB ? 0 : (f_) - S::TB;                                            \
+        const int nb_ = (f_) < TBc ? 0 : (f_) - TBc;                                                \
         const int brow_ = GATEUP ? ((nb_ < S::NBH ? 0 : BN / 2) + wn * (S::WTN / 2) + (nb_ % S::NBH) * 32) \
                                  : (wn * S::WTN + nb_ * 32);                                         \
         fb_[nb_] = as_bf16x8(*reinterpret_cast<const u32x4*>(                                        \
@@ -204,29 +206,29 @@ __global__ __launch_bounds__(256, OCC) void expert_tile_kernel(GemmArgs a) {
       }                                                                                             \
     }
 #define MOE_TILE_READ(fa_, fb_, stage_, kk_)                                                        \
-    { _Pragma("unroll") for (int f = 0; f < S::NF; ++f) MOE_TILE_READ1(fa_, fb_, stage_, kk_, f); }
+    { _Pragma("unroll") for (int f = 0; f < NFc; ++f) MOE_TILE_READ1(fa_, fb_, stage_, kk_, f); }
 #define MOE_TILE_MFMA1(fa_, fb_, j_)                                                                \
     acc[(j_) % S::NB][(j_) / S::NB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                       \
         fb_[(j_) % S::NB], fa_[(j_) / S::NB], acc[(j_) % S::NB][(j_) / S::NB], 0, 0, 0);
 #define MOE_TILE_MMA(fa_, fb_)                                                                      \
-    { _Pragma("unroll") for (int j = 0; j < S::NM; ++j) MOE_TILE_MFMA1(fa_, fb_, j); }
+    { _Pragma("unroll") for (int j = 0; j < NMc; ++j) MOE_TILE_MFMA1(fa_, fb_, j); }
     // One K slice: multiply the fragments in set X and, spread between the MFMAs, read the
     // fragments of slice kk_ of stage_ into set Y.  The scheduling fences pin that interleaving, so
     // no LDS read is issued in front of an idle matrix pipe.
 #define MOE_TILE_SLICE(faX, fbX, faY, fbY, stage_, kk_)                                             \
-    { _Pragma("unroll") for (int j = 0; j < S::NM; ++j) {                                           \
+    { _Pragma("unroll") for (int j = 0; j < NMc; ++j) {                                             \
         MOE_TILE_MFMA1(faX, fbX, j);                                                                \
-        _Pragma("unroll") for (int f = 0; f < S::NF; ++f)                                           \
-          if (f * S::NM / S::NF == j) MOE_TILE_READ1(faY, fbY, stage_, kk_, f);                      \
+        _Pragma("unroll") for (int f = 0; f < NFc; ++f)                                             \
+          if (f * NMc / NFc == j) MOE_TILE_READ1(faY, fbY, stage_, kk_, f);                          \
         __builtin_amdgcn_sched_barrier(0x6);                                                        \
     } }
     // Last slice of a stage: multiply set B; between the MFMAs first request the copies of the stage
     // that reuses the buffer just freed, then read slice 0 of the next stage into set A.
 #define MOE_TILE_SLICE_LAST(next_stage_, kt_issue_, st_issue_)                                      \
-    { _Pragma("unroll") for (int j = 0; j < S::NM; ++j) {                                           \
+    { _Pragma("unroll") for (int j = 0; j < NMc; ++j) {                                             \
         MOE_TILE_MFMA1(faB, fbB, j);                                                                \
-        _Pragma("unroll") for (int q = 0; q < S::NL + S::NF; ++q)                                   \
-          if (q * S::NM / (S::NL + S::NF) == j) {                                                   \
+        _Pragma("unroll") for (int q = 0; q < S::NL + NFc; ++q)                                     \
+          if (q * NMc / (S::NL + NFc) == j) {                                                       \
             if (q < S::NL) { MOE_TILE_ISSUE1(kt_issue_, st_issue_, q < S::NL ? q : 0); }             \
             else MOE_TILE_READ1(faA, fbA, next_stage_, 0, q < S::NL ? 0 : q - S::NL);               \
           }                                                                                         \
@@ -240,36 +242,58 @@ __global__ __launch_bounds__(256, OCC) void expert_tile_kernel(GemmArgs a) {
     // completely, so its buffer can take the copy of stage kt+NS.
     // (Past the end of K the requests repeat the last K step into a buffer nobody reads again:
     // every iteration then issues the same number of copies and the wait counts stay constant.)
+    auto pipeline = [&](auto tbc_) {
+      constexpr int TBc = decltype(tbc_)::value;
+      constexpr int NMc = TBc * S::NB;   // MFMAs per 16-wide K slice
+      constexpr int NFc = TBc + S::NB;   // operand fragments per slice
 #pragma unroll
-    for (int s = 0; s < NS; ++s) MOE_TILE_ISSUE(min(s, nk - 1), s);
-    wait_copies_but<S::DIST * S::NL>();
-    workgroup_barrier();
-    bf16x8 faA[S::TB], fbA[S::NB], faB[S::TB], fbB[S::NB];
-    MOE_TILE_READ(faA, fbA, 0, 0);
-    int st = 0;                                  // buffer of the stage being multiplied: kt % NS
-    for (int kt = 0; kt + 1 < nk; ++kt) {
-      const int st1 = st + 1 == NS ? 0 : st + 1;
+      for (int s = 0; s < NS; ++s) MOE_TILE_ISSUE(min(s, nk - 1), s);
+      wait_copies_but<S::DIST * S::NL>();
+      workgroup_barrier();
+      bf16x8 faA[S::TB], fbA[S::NB], faB[S::TB], fbB[S::NB];
+      MOE_TILE_READ(faA, fbA, 0, 0);
+      int st = 0;                                  // buffer of the stage being multiplied: kt % NS
+      for (int kt = 0; kt + 1 < nk; ++kt) {
+        const int st1 = st + 1 == NS ? 0 : st + 1;
+        MOE_TILE_SLICE(faA, fbA, faB, fbB, st, 1);
+        MOE_TILE_SLICE(faB, fbB, faA, fbA, st, 2);
+        MOE_TILE_SLICE(faA, fbA, faB, fbB, st, 3);
+        // this wave has finished reading stage kt once the last-slice fragments are in registers
+        // (the empty asm makes the compiler wait for them; the fence keeps that wait behind the MFMAs)
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int tb = 0; tb < TBc; ++tb) asm volatile("" : "+v"(faB[tb]));
+#pragma unroll
+        for (int nb = 0; nb < S::NB; ++nb) asm volatile("" : "+v"(fbB[nb]));
+        wait_copies_but<(S::DIST - 1) * S::NL>();
+        workgroup_barrier();  // stage kt+1 is complete for everyone; stage kt is free for everyone
+        MOE_TILE_SLICE_LAST(st1, min(kt + NS, nk - 1), st);
+        st = st1;
+      }
       MOE_TILE_SLICE(faA, fbA, faB, fbB, st, 1);
       MOE_TILE_SLICE(faB, fbB, faA, fbA, st, 2);
       MOE_TILE_SLICE(faA, fbA, faB, fbB, st, 3);
-      // this wave has finished reading stage kt once the last-slice fragments are in registers
-      // (the empty asm makes the compiler wait for them; the fence keeps that wait behind the MFMAs)
-      __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int tb = 0; tb < S::TB; ++tb) asm volatile("" : "+v"(faB[tb]));
-#pragma unroll
-      for (int nb = 0; nb < S::NB; ++nb) asm volatile("" : "+v"(fbB[nb]));
-      wait_copies_but<(S::DIST - 1) * S::NL>();
-      workgroup_barrier();  // stage kt+1 is complete for everyone; stage kt is free for everyone
-      MOE_TILE_SLICE_LAST(st1, min(kt + NS, nk - 1), st);
-      st = st1;
+      MOE_TILE_MMA(faB, fbB);
+      wait_lds_reads();
+      workgroup_barrier();   // the next tile's first copies overwrite stages other waves may still read
+    };
+    // token blocks of this wave that hold rows of the expert (at least one, so that the copies and
+    // operand reads keep their places between MFMAs)
+    const int tbv = min(S::TB, max(1, (rowsValid - wm * S::WTM + 31) >> 5));
+    if constexpr (S::TB == 1) {
+      pipeline(std::integral_constant<int, 1>{});
+    } else if constexpr (S::TB == 2) {
+      if (tbv == 1) pipeline(std::integral_constant<int, 1>{});
+      else pipeline(std::integral_constant<int, 2>{});
+    } else {
+      static_assert(S::TB == 4, "token blocks per wave");
+      switch (tbv) {
+        case 1: pipeline(std::integral_constant<int, 1>{}); break;
+        case 2: pipeline(std::integral_constant<int, 2>{}); break;
+        case 3: pipeline(std::integral_constant<int, 3>{}); break;
+        default: pipeline(std::integral_constant<int, 4>{}); break;
+      }
     }
-    MOE_TILE_SLICE(faA, fbA, faB, fbB, st, 1);
-    MOE_TILE_SLICE(faB, fbB, faA, fbA, st, 2);
-    MOE_TILE_SLICE(faA, fbA, faB, fbB, st, 3);
-    MOE_TILE_MMA(faB, fbB);
-    wait_lds_reads();
-    workgroup_barrier();   // the next tile's first copies overwrite stages other waves may still read
 #undef MOE_TILE_READ1
 #undef MOE_TILE_MFMA1
 #undef MOE_TILE_SLICE
