@@ -83,6 +83,12 @@ def main() -> int:
     ap.add_argument("--fused-gather", type=int, default=1,
                     help="1 (default): no permuted copy of the tokens, the block calls read x through src_of_row; "
                          "0: moe_permute writes Xp and the block calls read it")
+    ap.add_argument("--orchestrator", default="shared", choices=["shared", "private"],
+                    help="tenants workload: 'shared' = one orchestrator batches all tenants' tokens into one "
+                         "micro-batch per expert block (Sec. 3, Sec. 4.1); 'private' = one orchestrator per tenant, "
+                         "each with its own gating, micro-batches, block invocations and aggregation")
+    ap.add_argument("--tenant-streams", type=int, default=1,
+                    help="private orchestrators: issue the tenants' layers round-robin over this many streams")
     ap.add_argument("--no-graph", action="store_true")
     ap.add_argument("--overlap-shared", type=int, default=-1,
                     help="1: shared expert on a second stream, concurrent with the routed path; 0: one stream; "
@@ -201,7 +207,38 @@ def main() -> int:
             events.append(ev)
         moe.moe_combine(buf.Yp, buf.row_of_pair, buf.topk_w, buf.S, buf.sg, buf.out)
 
+    private = args.orchestrator == "private"
+    if private and wl.tenant_rows is None:
+        print("bench.py: --orchestrator private needs the tenants workload", file=sys.stderr)
+        return 2
+    if private:
+        tbufs = [moe.LayerBuffers.allocate(b - a, s.H, s.E, s.K, s.I, s.Is) for a, b in wl.tenant_rows]
+        tstreams = [torch.cuda.Stream() for _ in range(args.tenant_streams)] if args.tenant_streams > 1 else []
+
+    def tenant_layer(i, a, b):
+        w = layer_w[0]
+        moe.moe_layer_forward(g.x[a:b], w["Wr"], w["bias"][i:i + 1], w["Wg"], w["Wu"], w["Wd"], shared, s.K, s.renorm,
+                              groups=groups, buf=tbufs[i], tenant_rows=[(0, b - a)], policy=args.policy,
+                              shared_policy=args.shared_policy, fused_gather=fused)
+
+    def step_private():
+        """Every tenant's tokens go through their own gating, micro-batching, block calls and aggregation."""
+        if not tstreams:
+            for i, (a, b) in enumerate(wl.tenant_rows):
+                tenant_layer(i, a, b)
+            return
+        main = torch.cuda.current_stream()
+        for st in tstreams:
+            st.wait_stream(main)
+        for i, (a, b) in enumerate(wl.tenant_rows):
+            with torch.cuda.stream(tstreams[i % len(tstreams)]):
+                tenant_layer(i, a, b)
+        for st in tstreams:
+            main.wait_stream(st)
+
     def step(events=None):
+        if private and events is None:
+            return step_private()
         x = g.x
         for w in layer_w:
             layer_step(x, w, events)
@@ -228,6 +265,13 @@ def main() -> int:
         step(events)
     torch.cuda.synchronize()
     eager_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    if private:   # the per-kernel events above are those of the shared orchestrator; time the private step itself
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        eager_ms = (time.perf_counter() - t0) * 1e3 / args.steps
     kern_ms = {}
     for i, n in enumerate(names):
         if shared is None and i >= 2:
@@ -306,6 +350,9 @@ def main() -> int:
                    "policy": args.policy, "shared_policy": args.shared_policy,
                    "launch": "hip graph replay" if graph_ms is not None else "eager",
                    "block_streams": max(1, args.block_streams),
+                   "orchestrator": (f"private: {len(wl.tenant_rows)} tenants, each its own layer pass over "
+                                    f"{max(1, args.tenant_streams)} stream(s); per-kernel figures are the shared orchestrator's"
+                                    if private else "shared"),
                    "token_gather": "inside the gate/up kernel (no permuted copy)" if fused else "permuted copy Xp",
                    "shared_expert_stream": "second stream, concurrent with the routed path" if overlap else "same stream",
                    "active_experts": active, "rows_per_expert_max": int(counts.max()),

@@ -420,6 +420,27 @@ def test_block_size_does_not_change_the_result_bitwise(moe, oracle64):
     check_close(f64(buf.out)[tok], np.stack(refs), "multi-tenant layer output on sampled tokens")
 
 
+def test_private_orchestrators_agree_with_the_shared_one(moe, oracle64):
+    # Sec. 3: one orchestrator per tenant (own gating, micro-batches, block calls, aggregation) and one
+    # orchestrator batching all tenants compute the same per-token function: routing bit-equal, outputs
+    # equal up to the summation order of the kernels each batch size selects
+    wl = workloads.tenants(seed=13, n_tenants=3, T_per=96, H=256, I=128, Is=256, E=12)
+    s = wl.shape
+    g = wl.to("cuda")
+    sh = (g.Wsg, g.Wsu, g.Wsd, g.wgate)
+    shared_buf = moe.moe_layer_forward(g.x, g.Wr, g.bias, g.Wg, g.Wu, g.Wd, sh, s.K, s.renorm,
+                                       tenant_rows=wl.tenant_rows)
+    d = wl.f32_numpy()
+    for i, (a, b) in enumerate(wl.tenant_rows):
+        pb = moe.moe_layer_forward(g.x[a:b], g.Wr, g.bias[i], g.Wg, g.Wu, g.Wd, sh, s.K, s.renorm,
+                                   groups=workloads.partition(s.E, 5), fused_gather=True)
+        torch.cuda.synchronize()
+        assert torch.equal(pb.topk_ids, shared_buf.topk_ids[a:b])
+        ref = oracle64.layer(d["x"][a:b], d["Wr"], d["bias"][i], d["Wg"], d["Wu"], d["Wd"], shared_of(d), s.K, s.renorm)
+        check_close(f64(pb.out), ref["out"], f"tenant {i}, private orchestrator")
+        check_close(f64(shared_buf.out)[a:b], ref["out"], f"tenant {i}, shared orchestrator")
+
+
 def test_empty_and_degenerate_inputs(moe, oracle64):
     # every token to the same K experts: E - K experts are empty
     wl = workloads.decode(seed=41, T=70, H=128, E=16, I=64, Is=0)
