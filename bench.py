@@ -83,6 +83,9 @@ def main() -> int:
     ap.add_argument("--fused-gather", type=int, default=1,
                     help="1 (default): no permuted copy of the tokens, the block calls read x through src_of_row; "
                          "0: moe_permute writes Xp and the block calls read it")
+    ap.add_argument("--balanced-blocks", type=int, default=0,
+                    help="with --group-size g: form the E/g blocks by observed load (rows per expert of a warm-up "
+                         "step, heaviest expert first to the lightest block) instead of as id ranges")
     ap.add_argument("--orchestrator", default="shared", choices=["shared", "private"],
                     help="tenants workload: 'shared' = one orchestrator batches all tenants' tokens into one "
                          "micro-batch per expert block (Sec. 3, Sec. 4.1); 'private' = one orchestrator per tenant, "
@@ -149,7 +152,13 @@ def main() -> int:
 
     fused = bool(args.fused_gather)
 
+    block_lists = None     # per block an int32 device tensor of expert ids (load-balanced blocks)
+
     def block_call(x, w, lo, hi, policy):
+        if block_lists is not None:
+            moe.moe_expert_list_forward(block_lists[lo], x if fused else buf.Xp, buf.src_of_row if fused else None, s.K,
+                                        buf.expert_offsets, w["Wg"], w["Wu"], w["Wd"], buf.Yp, buf.workspace, policy)
+            return
         if fused:
             moe.moe_expert_group_forward_gather(lo, hi, x, buf.src_of_row, s.K, buf.expert_offsets, w["Wg"], w["Wu"],
                                                 w["Wd"], buf.Yp, buf.workspace, policy)
@@ -249,6 +258,17 @@ def main() -> int:
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    if args.balanced_blocks and len(groups) > 1 and not stack:
+        # the load observed in the warm-up steps decides the blocks of the timed steps (same batch here)
+        observed = torch.diff(buf.expert_offsets).cpu().tolist()
+        lists = moe.balanced_blocks(observed, len(groups))
+        block_lists = [torch.tensor(b, dtype=torch.int32, device="cuda") for b in lists]
+        block_rows = [sum(observed[e] for e in b) for b in lists]
+        range_rows = [sum(observed[lo:hi]) for lo, hi in groups]
+        groups = [(i, i + 1) for i in range(len(lists))]     # block_call indexes block_lists by lo
+        for _ in range(2):
+            step()
+        torch.cuda.synchronize()
     if args.calibration_copy_mib > 0:
         src = torch.ones(args.calibration_copy_mib << 20, dtype=torch.uint8, device="cuda")
         dst = torch.empty_like(src)
@@ -350,6 +370,8 @@ def main() -> int:
                    "policy": args.policy, "shared_policy": args.shared_policy,
                    "launch": "hip graph replay" if graph_ms is not None else "eager",
                    "block_streams": max(1, args.block_streams),
+                   "blocks": ({"formed": "by observed load", "rows_per_block": block_rows, "rows_per_range_block": range_rows}
+                              if block_lists is not None else "id ranges"),
                    "orchestrator": (f"private: {len(wl.tenant_rows)} tenants, each its own layer pass over "
                                     f"{max(1, args.tenant_streams)} stream(s); per-kernel figures are the shared orchestrator's"
                                     if private else "shared"),

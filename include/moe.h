@@ -183,6 +183,20 @@ int moe_expert_group_forward_gather(int group_lo, int group_hi, const void* x,
                                     void* workspace, size_t workspace_bytes, int policy,
                                     void* stream);
 
+/*
+ * An expert block given as a list of expert ids instead of an id range (Sec. 5 names adaptive,
+ * hot-expert-aware block formation as the next step: blocks formed by load need not be ranges).
+ * expert_ids [n_ids] int32 ON THE DEVICE, distinct values in [0,E) (not checked); the call
+ * computes exactly the rows of those experts, with the same result for each row as any other
+ * block cut.  tokens is Xp [P,H] when src_of_row is NULL, else x [P/K,H] read through
+ * src_of_row as in moe_expert_group_forward_gather.  policy as for moe_expert_group_forward_ex.
+ */
+int moe_expert_list_forward(const int32_t* expert_ids, int n_ids, const void* tokens,
+                            const int32_t* src_of_row, int K, const int32_t* expert_offsets,
+                            const void* Wg, const void* Wu, const void* Wd, int P, int H, int E,
+                            int I, void* Yp, void* workspace, size_t workspace_bytes, int policy,
+                            void* stream);
+
 /* Workspace sizes in bytes (multiples of 256). */
 size_t moe_permute_workspace_bytes(int T, int K, int E);
 size_t moe_expert_workspace_bytes(int P, int I);

@@ -17,7 +17,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB = None
 
 SYMBOLS = ["moe_status_string", "moe_route", "moe_permute", "moe_expert_group_forward",
-           "moe_expert_group_forward_ex", "moe_expert_group_forward_gather", "moe_shared_forward", "moe_shared_forward_ex", "moe_combine",
+           "moe_expert_group_forward_ex", "moe_expert_group_forward_gather", "moe_expert_list_forward",
+           "moe_shared_forward", "moe_shared_forward_ex", "moe_combine",
            "moe_permute_workspace_bytes", "moe_expert_workspace_bytes", "moe_shared_workspace_bytes",
            "moe_workspace_bytes", "moe_residual_norm"]
 
@@ -55,6 +56,9 @@ def load() -> ctypes.CDLL:
     lib.moe_expert_group_forward_gather.restype = c_int
     lib.moe_expert_group_forward_gather.argtypes = [c_int, c_int, c_vp, c_vp, c_int, c_vp, c_vp, c_vp, c_vp, c_int,
                                                     c_int, c_int, c_int, c_vp, c_vp, c_sz, c_int, c_vp]
+    lib.moe_expert_list_forward.restype = c_int
+    lib.moe_expert_list_forward.argtypes = [c_vp, c_int, c_vp, c_vp, c_int, c_vp, c_vp, c_vp, c_vp, c_int, c_int, c_int,
+                                            c_int, c_vp, c_vp, c_sz, c_int, c_vp]
     lib.moe_shared_forward.restype = c_int
     lib.moe_shared_forward.argtypes = [c_vp, c_vp, c_vp, c_vp, c_vp, c_int, c_int, c_int, c_vp, c_vp, c_vp, c_sz, c_vp]
     lib.moe_shared_forward_ex.restype = c_int
@@ -177,6 +181,40 @@ def moe_expert_group_forward_gather(group_lo: int, group_hi: int, x, src_of_row,
                                                 int(policy), _stream())
     _check(rc, "moe_expert_group_forward_gather")
     return Yp
+
+
+def moe_expert_list_forward(expert_ids, tokens, src_of_row, K: int, expert_offsets, Wg, Wu, Wd, Yp, workspace,
+                            policy: int = 0):
+    """Block invocation for the experts listed in expert_ids (int32 GPU tensor).  tokens is Xp when
+    src_of_row is None, else x (rows read through src_of_row)."""
+    E, I, H = Wg.shape
+    P = Yp.shape[0]
+    rc = load().moe_expert_list_forward(_ptr(expert_ids, torch.int32, "expert_ids"), int(expert_ids.numel()),
+                                        _ptr(tokens, torch.bfloat16, "tokens"),
+                                        _ptr(src_of_row, torch.int32, "src_of_row"), int(K),
+                                        _ptr(expert_offsets, torch.int32, "expert_offsets"),
+                                        _ptr(Wg, torch.bfloat16, "Wg"), _ptr(Wu, torch.bfloat16, "Wu"),
+                                        _ptr(Wd, torch.bfloat16, "Wd"), P, H, E, I,
+                                        _ptr(Yp, torch.bfloat16, "Yp"), _ptr(workspace, None, "workspace"),
+                                        0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                        int(policy), _stream())
+    _check(rc, "moe_expert_list_forward")
+    return Yp
+
+
+def balanced_blocks(rows_per_expert: Sequence[int], n_blocks: int) -> List[List[int]]:
+    """Hot-expert-aware block formation on the host: experts sorted by observed load (rows in a
+    previous batch) are dealt, heaviest first, to the block with the fewest rows so far.  Returns
+    n_blocks lists of expert ids (each ascending); every expert appears exactly once."""
+    n_blocks = max(1, min(int(n_blocks), len(rows_per_expert)))
+    order = sorted(range(len(rows_per_expert)), key=lambda e: (-int(rows_per_expert[e]), e))
+    blocks: List[List[int]] = [[] for _ in range(n_blocks)]
+    load_ = [0] * n_blocks
+    for e in order:
+        b = min(range(n_blocks), key=lambda i: (load_[i], len(blocks[i]), i))
+        blocks[b].append(e)
+        load_[b] += int(rows_per_expert[e])
+    return [sorted(b) for b in blocks]
 
 
 def moe_shared_forward(x, Wsg, Wsu, Wsd, wgate, S, sg, workspace, policy: int = 0):

@@ -81,7 +81,8 @@ int ffn_forward(const GemmArgs& gu, const GemmArgs& dn, const Plan& p, hipStream
   return rc;
 }
 
-int expert_group_forward_impl(int group_lo, int group_hi, const void* A, const int32_t* gather, int gather_div,
+int expert_group_forward_impl(int group_lo, int group_hi, const int32_t* ids, const void* A, const int32_t* gather,
+                              int gather_div,
                               const int32_t* expert_offsets, const void* Wg, const void* Wu, const void* Wd, int P,
                               int H, int E, int I, void* Yp, void* workspace, size_t workspace_bytes, int policy,
                               void* stream) {
@@ -95,7 +96,7 @@ int expert_group_forward_impl(int group_lo, int group_hi, const void* A, const i
   const Plan plan = make_plan(mean_rows, E, policy);
   GemmArgs gu{};
   gu.A = (const bf16_t*)A; gu.B0 = (const bf16_t*)Wg; gu.B1 = (const bf16_t*)Wu; gu.C = (bf16_t*)workspace;
-  gu.offsets = expert_offsets; gu.lo = group_lo; gu.hi = group_hi; gu.rows_fixed = 0; gu.rows_total = P;
+  gu.offsets = expert_offsets; gu.lo = group_lo; gu.hi = group_hi; gu.ids = ids; gu.rows_fixed = 0; gu.rows_total = P;
   gu.mean_rows = mean_rows; gu.N = I; gu.Kdim = H;
   GemmArgs dn = gu;
   gu.gather = gather; gu.gather_div = gather_div;   // only the first kernel reads token rows
@@ -166,7 +167,7 @@ int moe_permute(const int32_t* topk_ids, const void* x, int T, int H, int E, int
 int moe_expert_group_forward_ex(int group_lo, int group_hi, const void* Xp, const int32_t* expert_offsets,
                                 const void* Wg, const void* Wu, const void* Wd, int P, int H, int E, int I,
                                 void* Yp, void* workspace, size_t workspace_bytes, int policy, void* stream) {
-  return expert_group_forward_impl(group_lo, group_hi, Xp, nullptr, 1, expert_offsets, Wg, Wu, Wd, P, H, E, I, Yp,
+  return expert_group_forward_impl(group_lo, group_hi, nullptr, Xp, nullptr, 1, expert_offsets, Wg, Wu, Wd, P, H, E, I, Yp,
                                    workspace, workspace_bytes, policy, stream);
 }
 
@@ -176,8 +177,20 @@ int moe_expert_group_forward_gather(int group_lo, int group_hi, const void* x, c
                                     int policy, void* stream) {
   if (K < 1 || K > 16 || (P > 0 && P % K != 0)) return MOE_ERR_SHAPE;
   if (P > 0 && !src_of_row) return MOE_ERR_NULL;
-  return expert_group_forward_impl(group_lo, group_hi, x, src_of_row, K, expert_offsets, Wg, Wu, Wd, P, H, E, I, Yp,
-                                   workspace, workspace_bytes, policy, stream);
+  return expert_group_forward_impl(group_lo, group_hi, nullptr, x, src_of_row, K, expert_offsets, Wg, Wu, Wd, P, H, E, I,
+                                   Yp, workspace, workspace_bytes, policy, stream);
+}
+
+int moe_expert_list_forward(const int32_t* expert_ids, int n_ids, const void* tokens, const int32_t* src_of_row, int K,
+                            const int32_t* expert_offsets, const void* Wg, const void* Wu, const void* Wd, int P,
+                            int H, int E, int I, void* Yp, void* workspace, size_t workspace_bytes, int policy,
+                            void* stream) {
+  if (n_ids < 1 || n_ids > E) return MOE_ERR_SHAPE;
+  if (!expert_ids) return MOE_ERR_NULL;
+  if (src_of_row && (K < 1 || K > 16 || (P > 0 && P % K != 0))) return MOE_ERR_SHAPE;
+  // positions [0, n_ids) of the list take the place of the id range; the range checks see [0, n_ids)
+  return expert_group_forward_impl(0, n_ids, expert_ids, tokens, src_of_row, src_of_row ? K : 1, expert_offsets, Wg, Wu,
+                                   Wd, P, H, E, I, Yp, workspace, workspace_bytes, policy, stream);
 }
 
 int moe_expert_group_forward(int group_lo, int group_hi, const void* Xp, const int32_t* expert_offsets,

@@ -67,7 +67,8 @@ struct GemmArgs {
   const bf16_t* B1;    // weights of the up branch (gate/up kernels), else unused
   bf16_t* C;           // output rows [rows, N]
   const int32_t* offsets;  // expert_offsets on the device, or nullptr for one expert on rows [0, rows_fixed)
-  int lo, hi;          // experts [lo, hi)
+  int lo, hi;          // experts [lo, hi); with an id list: positions [lo, hi) of the list
+  const int32_t* ids;  // nullptr: expert id = position; else the block is the experts ids[lo .. hi) (device memory)
   int rows_fixed;
   int rows_total;      // number of rows of A and C (upper bound used to size the grid)
   int mean_rows;       // expected rows per expert (rows_total / experts of the layer): picks kernel shapes

@@ -43,9 +43,9 @@ __global__ __launch_bounds__(256) void expert_stream_kernel(GemmArgs a) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int nb_w = wave % NBW, ms_w = (wave / NBW) % MS, ks_w = wave / (NBW * MS);
   const int y = blockIdx.y;
-  const int eg = a.offsets ? a.lo + y : 0;
-  const int rb = a.offsets ? a.offsets[a.lo + y] : 0;
-  const int re = a.offsets ? a.offsets[a.lo + y + 1] : a.rows_fixed;
+  const int eg = a.offsets ? (a.ids ? a.ids[a.lo + y] : a.lo + y) : 0;
+  const int rb = a.offsets ? a.offsets[eg] : 0;
+  const int re = a.offsets ? a.offsets[eg + 1] : a.rows_fixed;
   const int Me = re - rb;
   if (Me <= 0) return;                         // whole workgroup: no barrier is skipped by part of it
 

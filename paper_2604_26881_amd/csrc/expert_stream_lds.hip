@@ -55,9 +55,9 @@ __global__ __launch_bounds__(64) void expert_stream_lds_kernel(GemmArgs a) {
 
   const int lane = threadIdx.x;
   const int y = blockIdx.y;
-  const int eg = a.offsets ? a.lo + y : 0;
-  const int rb = a.offsets ? a.offsets[a.lo + y] : 0;
-  const int re = a.offsets ? a.offsets[a.lo + y + 1] : a.rows_fixed;
+  const int eg = a.offsets ? (a.ids ? a.ids[a.lo + y] : a.lo + y) : 0;
+  const int rb = a.offsets ? a.offsets[eg] : 0;
+  const int re = a.offsets ? a.offsets[eg + 1] : a.rows_fixed;
   const int Me = re - rb;
   if (Me <= 0) return;
 

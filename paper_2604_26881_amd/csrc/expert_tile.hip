@@ -66,23 +66,30 @@ template <int BM, int BN, int WAVES_M, int WAVES_N, bool GATEUP, int NS, int OCC
 __global__ __launch_bounds__(256, OCC) void expert_tile_kernel(GemmArgs a) {
   using S = TileShape<BM, BN, WAVES_M, WAVES_N, GATEUP, NS>;
   extern __shared__ __align__(16) unsigned char smem[];
-  __shared__ int s_pref[TILE_EMAX + 1];
-  __shared__ int s_rb[TILE_EMAX + 1];
+  __shared__ int s_pref[TILE_EMAX + 1];   // token tiles before expert i of the block
+  __shared__ int s_rb[TILE_EMAX];         // first row of expert i of the block
+  __shared__ int s_re[TILE_EMAX];         // one past its last row
+  __shared__ int s_eid[TILE_EMAX];        // its expert id
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave / WAVES_N, wn = wave % WAVES_N;
   const int nexp = a.offsets ? a.hi - a.lo : 1;
 
-  // per-expert row begin and number of token tiles -> exclusive prefix in LDS
-  for (int i = tid; i <= nexp; i += 256) s_rb[i] = a.offsets ? a.offsets[a.lo + i] : (i == 0 ? 0 : a.rows_fixed);
+  // per-expert row range and number of token tiles -> exclusive prefix in LDS
+  for (int i = tid; i < nexp; i += 256) {
+    const int eid = a.offsets ? (a.ids ? a.ids[a.lo + i] : a.lo + i) : 0;
+    s_eid[i] = eid;
+    s_rb[i] = a.offsets ? a.offsets[eid] : 0;
+    s_re[i] = a.offsets ? a.offsets[eid + 1] : a.rows_fixed;
+  }
   __syncthreads();
   if (wave == 0) {
     int v[4], sum = 0;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int e = lane * 4 + i;
-      v[i] = e < nexp ? (s_rb[e + 1] - s_rb[e] + BM - 1) / BM : 0;
+      v[i] = e < nexp ? (s_re[e] - s_rb[e] + BM - 1) / BM : 0;
       sum += v[i];
     }
     int incl = sum;
@@ -145,10 +152,10 @@ __global__ __launch_bounds__(256, OCC) void expert_tile_kernel(GemmArgs a) {
     }
     const int e = elo;
     const int row0 = s_rb[e] + (mrow - s_pref[e]) * BM;
-    const int rowEnd = s_rb[e + 1];
+    const int rowEnd = s_re[e];
     const int rowsValid = min(BM, rowEnd - row0);
     const int n0 = nt * S::NOUT;
-    const int eg = a.offsets ? a.lo + e : 0;
+    const int eg = s_eid[e];
 
     const size_t kbeg = (size_t)ks * nk * S::BK;
     // with a gather list the token rows are addressed from the start of A, through the list
@@ -380,7 +387,7 @@ static int launch_tile_t(const GemmArgs& a, hipStream_t st) {
   static_assert(KSPLIT == 1 || !GATEUP, "the SwiGLU product needs complete sums");
   if (a.Kdim % (S::BK * KSPLIT) != 0) return -2;
   if (KSPLIT > 1 && a.Cpart == nullptr) return -3;
-  static_assert(OCC * (NS * S::STAGE + 2100) <= 160 * 1024, "LDS of the resident workgroups must fit a CU");
+  static_assert(OCC * (NS * S::STAGE + 4200) <= 160 * 1024, "LDS of the resident workgroups must fit a CU");
   static bool attr_set = false;
   const int lds = NS * S::STAGE;
   if (!attr_set) {

@@ -1,6 +1,8 @@
 """Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
 header declares, sizes its workspaces as documented and rejects bad arguments before any launch."""
 import ctypes
+
+import numpy as np
 import os
 import re
 
@@ -79,6 +81,14 @@ def test_bad_arguments_are_rejected_before_any_launch(lib):
     assert ga(p, 3, 32) == SHAPE          # P is not a multiple of K
     assert ga(p, 0, 32) == SHAPE
     assert ga(None, 2, 0) == 0            # P = 0: no-op
+    # expert block as an id list
+    li = lambda ids, n, src, K, P: lib.moe_expert_list_forward(ids, n, p, src, K, p, p, p, p, P, 64, 8, 128, p, p, 1 << 20,
+                                                               0, None)
+    assert li(None, 3, None, 1, 32) == NULL
+    assert li(p, 0, None, 1, 32) == SHAPE        # empty list
+    assert li(p, 9, None, 1, 32) == SHAPE        # more ids than experts
+    assert li(p, 3, p, 5, 32) == SHAPE           # gather form: P not a multiple of K
+    assert li(p, 3, None, 1, 0) == 0             # P = 0: no-op
     # shared expert
     assert lib.moe_shared_forward(p, p, p, p, p, 4, 64, 96, p, p, p, 1 << 20, None) == SHAPE
     assert lib.moe_shared_forward(p, p, p, p, p, 4, 64, 128, p, None, p, 1 << 20, None) == NULL
@@ -87,3 +97,18 @@ def test_bad_arguments_are_rejected_before_any_launch(lib):
     assert lib.moe_combine(p, p, p, p, None, 4, 64, 2, p, None) == NULL      # S without sg
     assert lib.moe_combine(p, p, p, None, None, 4, 64, 17, p, None) == SHAPE
     assert lib.moe_combine(None, p, p, None, None, 4, 64, 2, p, None) == NULL
+
+
+def test_balanced_blocks_partition_and_balance():
+    from paper_2604_26881_amd.binding import balanced_blocks
+    rng = np.random.default_rng(3)
+    for E, nb in ((60, 3), (60, 4), (60, 7), (8, 8), (5, 9), (1, 1)):
+        rows = (rng.zipf(1.3, size=E) % 500).tolist()
+        blocks = balanced_blocks(rows, nb)
+        assert len(blocks) == min(nb, E)
+        flat = sorted(e for b in blocks for e in b)
+        assert flat == list(range(E))                        # every expert exactly once
+        assert all(b == sorted(b) for b in blocks)
+        loads = [sum(rows[e] for e in b) for b in blocks]
+        assert max(loads) - min(loads) <= max(rows)          # greedy bound: spread at most one item
+    assert balanced_blocks([5, 5, 5, 5], 2) == [[0, 2], [1, 3]]

@@ -235,6 +235,44 @@ def test_block_calls_reading_x_through_src_of_row_equal_the_permuted_copy(moe, o
     check_close(f64(Yb), ref["Yp"], f"Yp, rows gathered by the kernel, policy {policy}")
 
 
+@pytest.mark.parametrize("policy", [0, 1, 5, 4, 9])
+def test_blocks_given_as_id_lists_equal_blocks_given_as_ranges(moe, policy):
+    # hot-expert-aware block formation hands out arbitrary id sets: same bits as any range cut
+    wl = skewed_workload(T=500, H=256, E=14, K=3, I=128, Is=0, seed=29)
+    s = wl.shape
+    g = wl.to("cuda")
+    ids, w = moe.moe_route(g.x, g.Wr, g.bias, s.K, s.renorm)
+    off, src, rowp, Xp = moe.moe_permute(ids, g.x, s.E)
+    ws = torch.empty(s.P * s.I * 2, dtype=torch.uint8, device="cuda")
+    Ya = torch.full((s.P, s.H), 768.0, dtype=torch.bfloat16, device="cuda")
+    moe.moe_expert_group_forward(0, s.E, Xp, off, g.Wg, g.Wu, g.Wd, Ya, ws, policy)
+    counts = torch.diff(off).cpu().tolist()
+    blocks = moe.balanced_blocks(counts, 3)
+    assert sorted(e for b in blocks for e in b) == list(range(s.E))
+    for gather in (False, True):
+        Yb = torch.full((s.P, s.H), 768.0, dtype=torch.bfloat16, device="cuda")
+        for b in blocks[::-1]:
+            lst = torch.tensor(b, dtype=torch.int32, device="cuda")
+            if gather:
+                moe.moe_expert_list_forward(lst, g.x, src, s.K, off, g.Wg, g.Wu, g.Wd, Yb, ws, policy)
+            else:
+                moe.moe_expert_list_forward(lst, Xp, None, s.K, off, g.Wg, g.Wu, g.Wd, Yb, ws, policy)
+        torch.cuda.synchronize()
+        assert torch.equal(Ya.view(torch.int16), Yb.view(torch.int16)), f"gather={gather}"
+    # one list alone touches only its experts' rows
+    Yc = torch.full((s.P, s.H), 768.0, dtype=torch.bfloat16, device="cuda")
+    lst = torch.tensor(blocks[0], dtype=torch.int32, device="cuda")
+    moe.moe_expert_list_forward(lst, Xp, None, s.K, off, g.Wg, g.Wu, g.Wd, Yc, ws, policy)
+    torch.cuda.synchronize()
+    offs = off.cpu().tolist()
+    mine = np.zeros(s.P, bool)
+    for e in blocks[0]:
+        mine[offs[e]:offs[e + 1]] = True
+    y = Yc.float().cpu().numpy()
+    assert np.all(y[~mine] == 768.0)
+    assert np.array_equal(Yc.view(torch.int16).cpu().numpy()[mine], Ya.view(torch.int16).cpu().numpy()[mine])
+
+
 def test_layer_with_fused_gather_at_decode_and_prefill_sizes(moe, oracle64):
     for wl in (workloads.decode(), workloads.prefill()):     # the sizes the benchmark times
         s = wl.shape
