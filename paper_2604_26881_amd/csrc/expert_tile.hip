@@ -53,6 +53,13 @@ struct TileShape {
   static constexpr int DIST = NS - 1;             // stages in flight while one is being multiplied
   static constexpr int NOUT = GATEUP ? BN / 2 : BN;  // output columns per tile
   static constexpr int GM = BN >= 256 ? 4 : 1;    // token tiles per locality group of the tile walk
+  // The NL copies of a stage are requested in three places, so that the address unit of the CU
+  // (one copy instruction of 1 KB keeps it busy for about 16 clocks) is not asked for a whole stage
+  // within one K slice: ISSUE0 of them while the last slice of the stage that frees the buffer is
+  // multiplied, ISSUE1 and ISSUE2 during the first two slices of the next K step.
+  static constexpr int ISSUE0 = NL - 2 * (NL / 3);
+  static constexpr int ISSUE1 = NL / 3;
+  static constexpr int ISSUE2 = NL / 3;
   static_assert(WAVES_M * WAVES_N == 4, "four waves per workgroup");
   static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile is made of 32x32 blocks");
   static_assert(!GATEUP || NB % 2 == 0, "gate and up blocks come in pairs");
@@ -229,15 +236,26 @@ __global__ __launch_bounds__(256, OCC) void expert_tile_kernel(GemmArgs a) {
           if (f * NMc / NFc == j) MOE_TILE_READ1(faY, fbY, stage_, kk_, f);                          \
         __builtin_amdgcn_sched_barrier(0x6);                                                        \
     } }
-    // Last slice of a stage: multiply set B; between the MFMAs first request the copies of the stage
-    // that reuses the buffer just freed, then read slice 0 of the next stage into set A.
+    // The same with copies I0 .. I1-1 of K step kt_issue_ (into buffer st_issue_) requested in between.
+#define MOE_TILE_SLICE_ISSUE(faX, fbX, faY, fbY, stage_, kk_, kt_issue_, st_issue_, I0, I1)         \
+    { _Pragma("unroll") for (int j = 0; j < NMc; ++j) {                                             \
+        MOE_TILE_MFMA1(faX, fbX, j);                                                                \
+        _Pragma("unroll") for (int q = 0; q < ((I1) - (I0)) + NFc; ++q)                             \
+          if (q * NMc / (((I1) - (I0)) + NFc) == j) {                                               \
+            if (q < (I1) - (I0)) { MOE_TILE_ISSUE1(kt_issue_, st_issue_, q < (I1) - (I0) ? (I0) + q : 0); } \
+            else MOE_TILE_READ1(faY, fbY, stage_, kk_, q < (I1) - (I0) ? 0 : q - ((I1) - (I0)));      \
+          }                                                                                         \
+        __builtin_amdgcn_sched_barrier(0x6);                                                        \
+    } }
+    // Last slice of a stage: multiply set B; between the MFMAs first request the first copies of the
+    // stage that reuses the buffer just freed, then read slice 0 of the next stage into set A.
 #define MOE_TILE_SLICE_LAST(next_stage_, kt_issue_, st_issue_)                                      \
     { _Pragma("unroll") for (int j = 0; j < NMc; ++j) {                                             \
         MOE_TILE_MFMA1(faB, fbB, j);                                                                \
-        _Pragma("unroll") for (int q = 0; q < S::NL + NFc; ++q)                                     \
-          if (q * NMc / (S::NL + NFc) == j) {                                                       \
-            if (q < S::NL) { MOE_TILE_ISSUE1(kt_issue_, st_issue_, q < S::NL ? q : 0); }             \
-            else MOE_TILE_READ1(faA, fbA, next_stage_, 0, q < S::NL ? 0 : q - S::NL);               \
+        _Pragma("unroll") for (int q = 0; q < S::ISSUE0 + NFc; ++q)                                 \
+          if (q * NMc / (S::ISSUE0 + NFc) == j) {                                                   \
+            if (q < S::ISSUE0) { MOE_TILE_ISSUE1(kt_issue_, st_issue_, q < S::ISSUE0 ? q : 0); }     \
+            else MOE_TILE_READ1(faA, fbA, next_stage_, 0, q < S::ISSUE0 ? 0 : q - S::ISSUE0);       \
           }                                                                                         \
         __builtin_amdgcn_sched_barrier(0x6);                                                        \
     } }
@@ -262,8 +280,12 @@ __global__ __launch_bounds__(256, OCC) void expert_tile_kernel(GemmArgs a) {
       int st = 0;                                  // buffer of the stage being multiplied: kt % NS
       for (int kt = 0; kt + 1 < nk; ++kt) {
         const int st1 = st + 1 == NS ? 0 : st + 1;
-        MOE_TILE_SLICE(faA, fbA, faB, fbB, st, 1);
-        MOE_TILE_SLICE(faB, fbB, faA, fbA, st, 2);
+        // the rest of the copies of K step kt-1+NS, whose first part went out during the last slice
+        // of K step kt-1 (at kt = 0 this repeats copies of the prologue: same bytes, same place)
+        const int ktd = min(kt - 1 + NS, nk - 1);
+        const int std_ = st == 0 ? NS - 1 : st - 1;
+        MOE_TILE_SLICE_ISSUE(faA, fbA, faB, fbB, st, 1, ktd, std_, S::ISSUE0, S::ISSUE0 + S::ISSUE1);
+        MOE_TILE_SLICE_ISSUE(faB, fbB, faA, fbA, st, 2, ktd, std_, S::ISSUE0 + S::ISSUE1, S::NL);
         MOE_TILE_SLICE(faA, fbA, faB, fbB, st, 3);
         // this wave has finished reading stage kt once the last-slice fragments are in registers
         // (the empty asm makes the compiler wait for them; the fence keeps that wait behind the MFMAs)
@@ -282,6 +304,7 @@ __global__ __launch_bounds__(256, OCC) void expert_tile_kernel(GemmArgs a) {
       MOE_TILE_SLICE(faA, fbA, faB, fbB, st, 3);
       MOE_TILE_MMA(faB, fbB);
       wait_lds_reads();
+      wait_copies_but<0>();  // the repeated last-step copies of the final iterations: none may outlive the tile
       workgroup_barrier();   // the next tile's first copies overwrite stages other waves may still read
     };
     // token blocks of this wave that hold rows of the expert (at least one, so that the copies and
@@ -305,6 +328,7 @@ __global__ __launch_bounds__(256, OCC) void expert_tile_kernel(GemmArgs a) {
 #undef MOE_TILE_MFMA1
 #undef MOE_TILE_SLICE
 #undef MOE_TILE_SLICE_LAST
+#undef MOE_TILE_SLICE_ISSUE
 #undef MOE_TILE_ISSUE1
 #undef MOE_TILE_READ
 #undef MOE_TILE_MMA
