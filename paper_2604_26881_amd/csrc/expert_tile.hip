@@ -69,6 +69,14 @@ struct TileShape {
 
 constexpr int TILE_EMAX = 256;
 
+// Order in which the operand fragments of a K slice are read: by the MFMA that needs them first.
+// MFMA j of a slice multiplies weight block j % NB with token block j / NB, so weight block 0 and
+// token block 0 come first, then the other weight blocks, then the token blocks.  Returns the
+// fragment number in the numbering "token blocks 0..TB-1, then weight blocks".
+__host__ __device__ constexpr int fragment_read_order(int slot, int tb, int nb) {
+  return slot == 0 ? tb : (slot == 1 ? 0 : (slot <= nb ? tb + slot - 1 : slot - nb));
+}
+
 template <int BM, int BN, int WAVES_M, int WAVES_N, bool GATEUP, int NS, int OCC, int KSPLIT>
 __global__ __launch_bounds__(256, OCC) void expert_tile_kernel(GemmArgs a) {
   using S = TileShape<BM, BN, WAVES_M, WAVES_N, GATEUP, NS>;
@@ -233,7 +241,7 @@ __global__ __launch_bounds__(256, OCC) void expert_tile_kernel(GemmArgs a) {
     { _Pragma("unroll") for (int j = 0; j < NMc; ++j) {                                             \
         MOE_TILE_MFMA1(faX, fbX, j);                                                                \
         _Pragma("unroll") for (int f = 0; f < NFc; ++f)                                             \
-          if (f * NMc / NFc == j) MOE_TILE_READ1(faY, fbY, stage_, kk_, f);                          \
+          if (f * NMc / NFc == j) MOE_TILE_READ1(faY, fbY, stage_, kk_, fragment_read_order(f, TBc, S::NB)); \
         __builtin_amdgcn_sched_barrier(0x6);                                                        \
     } }
     // The same with copies I0 .. I1-1 of K step kt_issue_ (into buffer st_issue_) requested in between.
@@ -242,8 +250,11 @@ __global__ __launch_bounds__(256, OCC) void expert_tile_kernel(GemmArgs a) {
         MOE_TILE_MFMA1(faX, fbX, j);                                                                \
         _Pragma("unroll") for (int q = 0; q < ((I1) - (I0)) + NFc; ++q)                             \
           if (q * NMc / (((I1) - (I0)) + NFc) == j) {                                               \
-            if (q < (I1) - (I0)) { MOE_TILE_ISSUE1(kt_issue_, st_issue_, q < (I1) - (I0) ? (I0) + q : 0); } \
-            else MOE_TILE_READ1(faY, fbY, stage_, kk_, q < (I1) - (I0) ? 0 : q - ((I1) - (I0)));      \
+            constexpr int NE_ = S::NB + 1 < NFc ? S::NB + 1 : NFc;   /* reads needed early: before the copies */ \
+            constexpr int NC_ = (I1) - (I0);                                                        \
+            if (q < NE_) MOE_TILE_READ1(faY, fbY, stage_, kk_, fragment_read_order(q < NE_ ? q : 0, TBc, S::NB)) \
+            else if (q < NE_ + NC_) { MOE_TILE_ISSUE1(kt_issue_, st_issue_, (q >= NE_ && q < NE_ + NC_) ? (I0) + q - NE_ : 0); } \
+            else MOE_TILE_READ1(faY, fbY, stage_, kk_, fragment_read_order(q >= NE_ + NC_ ? q - NC_ : 0, TBc, S::NB)) \
           }                                                                                         \
         __builtin_amdgcn_sched_barrier(0x6);                                                        \
     } }
@@ -254,8 +265,10 @@ __global__ __launch_bounds__(256, OCC) void expert_tile_kernel(GemmArgs a) {
         MOE_TILE_MFMA1(faB, fbB, j);                                                                \
         _Pragma("unroll") for (int q = 0; q < S::ISSUE0 + NFc; ++q)                                 \
           if (q * NMc / (S::ISSUE0 + NFc) == j) {                                                   \
-            if (q < S::ISSUE0) { MOE_TILE_ISSUE1(kt_issue_, st_issue_, q < S::ISSUE0 ? q : 0); }     \
-            else MOE_TILE_READ1(faA, fbA, next_stage_, 0, q < S::ISSUE0 ? 0 : q - S::ISSUE0);       \
+            constexpr int NE_ = S::NB + 1 < NFc ? S::NB + 1 : NFc;                                  \
+            if (q < NE_) MOE_TILE_READ1(faA, fbA, next_stage_, 0, fragment_read_order(q < NE_ ? q : 0, TBc, S::NB)) \
+            else if (q < NE_ + S::ISSUE0) { MOE_TILE_ISSUE1(kt_issue_, st_issue_, (q >= NE_ && q < NE_ + S::ISSUE0) ? q - NE_ : 0); } \
+            else MOE_TILE_READ1(faA, fbA, next_stage_, 0, fragment_read_order(q >= NE_ + S::ISSUE0 ? q - S::ISSUE0 : 0, TBc, S::NB)) \
           }                                                                                         \
         __builtin_amdgcn_sched_barrier(0x6);                                                        \
     } }
