@@ -149,15 +149,36 @@ __global__ __launch_bounds__(256, OCC) void expert_tile_kernel(GemmArgs a) {
   const int slot = xcd_walk ? (int)(blockIdx.x >> 3) : 0;
   const int run = xcd_walk ? max(1, min(G >> 3, (Lend + 7) >> 3)) : 1;
   if (xcd_walk && slot >= run) return;
-  for (int it = 0;; ++it) {
-    const int L = xcd_walk ? ((it * 8 + (int)(blockIdx.x & 7)) * run + slot) : (it * G + (int)blockIdx.x);
-    if (L >= Lend) break;
-    const int ks = KSPLIT > 1 ? L % KSPLIT : 0;   // K part of this work item
-    const int Lt = KSPLIT > 1 ? L / KSPLIT : L;
-    const int grp = Lt / groupTiles, rem = Lt - grp * groupTiles;
-    const int mrow = grp * S::GM + rem % S::GM;
-    const int nt = rem / S::GM;
-    if (mrow >= totalM) continue;
+
+    // copy i (of NL) of K step kt into stage buffer st; all NL of them
+#define MOE_TILE_ISSUE1(kt, st, i)                                                                  \
+    copy_to_lds_16(((i) < S::NLA ? Ag : ((GATEUP && (i) >= S::NLA + (S::NL - S::NLA) / 2) ? Bg1 : Bg0)) + (size_t)(kt) * S::ROWB, \
+                   coff[i], lds0 + (uint32_t)(st) * S::STAGE + (uint32_t)wave * 1024u + (uint32_t)(i) * 4096u);
+#define MOE_TILE_ISSUE(kt, st)                                                                      \
+    { _Pragma("unroll") for (int i = 0; i < S::NL; ++i) MOE_TILE_ISSUE1(kt, st, i); }
+
+  // State of a tile: the current one (being multiplied, then stored) and, while the current one is
+  // stored, the next one, whose first NS stages are already requested: the latency of those copies
+  // hides behind the epilogue instead of opening every tile.
+  struct TileState { int row0, rowEnd, rowsValid, n0, ks; bool valid; };
+  const unsigned char *Ag = nullptr, *Bg0 = nullptr, *Bg1 = nullptr;
+  uint32_t coff[S::NL];   // byte offsets of this lane's 16 bytes for each of the NL copies of a stage (K step 0)
+  int it = 0;
+  auto next_tile = [&]() -> TileState {
+    TileState t{};
+    int L = 0, mrow = 0, nt = 0;
+    for (;; ++it) {
+      L = xcd_walk ? ((it * 8 + (int)(blockIdx.x & 7)) * run + slot) : (it * G + (int)blockIdx.x);
+      if (L >= Lend) { t.valid = false; return t; }
+      const int Lt = KSPLIT > 1 ? L / KSPLIT : L;
+      const int grp = Lt / groupTiles, rem = Lt - grp * groupTiles;
+      mrow = grp * S::GM + rem % S::GM;
+      nt = rem / S::GM;
+      if (mrow < totalM) break;
+    }
+    ++it;
+    t.valid = true;
+    t.ks = KSPLIT > 1 ? L % KSPLIT : 0;   // K part of this work item
 
     // expert of this token tile: last e with s_pref[e] <= mrow
     int elo = 0, ehi = nexp;
@@ -166,34 +187,40 @@ __global__ __launch_bounds__(256, OCC) void expert_tile_kernel(GemmArgs a) {
       if (s_pref[mid] <= mrow) elo = mid; else ehi = mid;
     }
     const int e = elo;
-    const int row0 = s_rb[e] + (mrow - s_pref[e]) * BM;
-    const int rowEnd = s_re[e];
-    const int rowsValid = min(BM, rowEnd - row0);
-    const int n0 = nt * S::NOUT;
+    t.row0 = s_rb[e] + (mrow - s_pref[e]) * BM;
+    t.rowEnd = s_re[e];
+    t.rowsValid = min(BM, t.rowEnd - t.row0);
+    t.n0 = nt * S::NOUT;
     const int eg = s_eid[e];
 
-    const size_t kbeg = (size_t)ks * nk * S::BK;
+    const size_t kbeg = (size_t)t.ks * nk * S::BK;
     // with a gather list the token rows are addressed from the start of A, through the list
-    const unsigned char* Ag = reinterpret_cast<const unsigned char*>(a.A + (a.gather ? (size_t)0 : (size_t)row0 * Kdim) + kbeg);
-    const unsigned char* Bg0 = reinterpret_cast<const unsigned char*>(a.B0 + (size_t)eg * a.N * Kdim + kbeg);
-    const unsigned char* Bg1 = GATEUP ? reinterpret_cast<const unsigned char*>(a.B1 + (size_t)eg * a.N * Kdim + kbeg) : nullptr;
-    // byte offsets of this lane's 16 bytes for each of the NL copies of a stage (K step 0)
-    uint32_t coff[S::NL];
+    Ag = reinterpret_cast<const unsigned char*>(a.A + (a.gather ? (size_t)0 : (size_t)t.row0 * Kdim) + kbeg);
+    Bg0 = reinterpret_cast<const unsigned char*>(a.B0 + (size_t)eg * a.N * Kdim + kbeg);
+    Bg1 = GATEUP ? reinterpret_cast<const unsigned char*>(a.B1 + (size_t)eg * a.N * Kdim + kbeg) : nullptr;
 #pragma unroll
     for (int i = 0; i < S::NL; ++i) {
       const int row = (i * 4 + wave) * 8 + crow;        // row inside the stage: tokens first, then weights
       int grow;
       if (i < S::NLA) {
-        grow = min(row, rowsValid - 1);
-        if (a.gather) grow = a.gather[row0 + grow] / a.gather_div;
+        grow = min(row, t.rowsValid - 1);
+        if (a.gather) grow = a.gather[t.row0 + grow] / a.gather_div;
       } else {
         int r = row - BM;
         if (GATEUP && i >= S::NLA + (S::NL - S::NLA) / 2) r -= BN / 2;   // second half: the up branch
-        grow = min(n0 + r, a.N - 1);
+        grow = min(t.n0 + r, a.N - 1);
       }
       coff[i] = (uint32_t)grow * (uint32_t)Kdim * 2u + (uint32_t)cchunk * 16u;
     }
+    // all NS stages of the tile are requested up front
+#pragma unroll
+    for (int s = 0; s < NS; ++s) MOE_TILE_ISSUE(min(s, nk - 1), s);
+    return t;
+  };
 
+  TileState cur = next_tile();
+  while (cur.valid) {
+    const int row0 = cur.row0, rowEnd = cur.rowEnd, rowsValid = cur.rowsValid, n0 = cur.n0, ks = cur.ks;
     f32x16 acc[S::NB][S::TB];
 #pragma unroll
     for (int nb = 0; nb < S::NB; ++nb)
@@ -201,13 +228,6 @@ __global__ __launch_bounds__(256, OCC) void expert_tile_kernel(GemmArgs a) {
       for (int tb = 0; tb < S::TB; ++tb)
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[nb][tb][i] = 0.0f;
-
-    // copy i (of NL) of K step kt into stage buffer st; all NL of them
-#define MOE_TILE_ISSUE1(kt, st, i)                                                                  \
-    copy_to_lds_16(((i) < S::NLA ? Ag : ((GATEUP && (i) >= S::NLA + (S::NL - S::NLA) / 2) ? Bg1 : Bg0)) + (size_t)(kt) * S::ROWB, \
-                   coff[i], lds0 + (uint32_t)(st) * S::STAGE + (uint32_t)wave * 1024u + (uint32_t)(i) * 4096u);
-#define MOE_TILE_ISSUE(kt, st)                                                                      \
-    { _Pragma("unroll") for (int i = 0; i < S::NL; ++i) MOE_TILE_ISSUE1(kt, st, i); }
 
     // fragment f of the 16-wide K slice kk_ of a stage, LDS -> registers: f < TBc is the token block
     // f, otherwise the weight block f - TBc.  TBc <= TB is the number of 32-row token blocks of this
@@ -273,7 +293,7 @@ __global__ __launch_bounds__(256, OCC) void expert_tile_kernel(GemmArgs a) {
         __builtin_amdgcn_sched_barrier(0x6);                                                        \
     } }
 
-    // Pipeline.  All NS stages are requested up front; while stage kt is multiplied, stages
+    // Pipeline.  All NS stages have been requested (next_tile); while stage kt is multiplied, stages
     // kt+1 .. kt+NS-1 are in flight.  Fragment sets A and B alternate over the four slices of a
     // stage; slice 0 of the NEXT stage is read (after the barrier that publishes it) while the last
     // slice is multiplied.  That barrier also tells every wave that stage kt has been read
@@ -284,9 +304,7 @@ __global__ __launch_bounds__(256, OCC) void expert_tile_kernel(GemmArgs a) {
       constexpr int TBc = decltype(tbc_)::value;
       constexpr int NMc = TBc * S::NB;   // MFMAs per 16-wide K slice
       constexpr int NFc = TBc + S::NB;   // operand fragments per slice
-#pragma unroll
-      for (int s = 0; s < NS; ++s) MOE_TILE_ISSUE(min(s, nk - 1), s);
-      wait_copies_but<S::DIST * S::NL>();
+      wait_copies_but<S::DIST * S::NL>();   // stage 0 (requested before the previous tile was stored) has landed
       workgroup_barrier();
       bf16x8 faA[S::TB], fbA[S::NB], faB[S::TB], fbB[S::NB];
       MOE_TILE_READ(faA, fbA, 0, 0);
@@ -342,10 +360,12 @@ __global__ __launch_bounds__(256, OCC) void expert_tile_kernel(GemmArgs a) {
 #undef MOE_TILE_SLICE
 #undef MOE_TILE_SLICE_LAST
 #undef MOE_TILE_SLICE_ISSUE
-#undef MOE_TILE_ISSUE1
 #undef MOE_TILE_READ
 #undef MOE_TILE_MMA
-#undef MOE_TILE_ISSUE
+
+    // the stage buffers are free (final barrier of the pipeline): request the next tile's first
+    // stages now, their way from L2 overlaps the stores below
+    const TileState nxt = next_tile();
 
     // epilogue: accumulator element i of block (nb, tb) is output column
     // 8*(i/4) + 4*(lane/32) + i%4 of the block, token row lane%32.
@@ -386,7 +406,10 @@ __global__ __launch_bounds__(256, OCC) void expert_tile_kernel(GemmArgs a) {
         }
       }
     }
+    cur = nxt;
   }
+#undef MOE_TILE_ISSUE1
+#undef MOE_TILE_ISSUE
 }
 
 static int num_cus() {
