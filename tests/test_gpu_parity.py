@@ -355,6 +355,22 @@ def test_combine_matches_oracle(moe, oracle64):
     check_close(f64(out), ref, "combine without shared", tight=4e-3)
 
 
+def test_bf16_rounding_is_to_nearest_even(moe):
+    # out = bf16(1*Yp[a] + 1*Yp[b]): the fp32 sum of two bf16 values is exact for these magnitudes, so the
+    # result must be torch's round-to-nearest-even conversion bit for bit (ties included)
+    T, H, K = 64, 512, 2
+    g = torch.Generator().manual_seed(17)
+    Yp = (torch.randn((T * K, H), generator=g) * torch.logspace(-3, 3, H)).to(torch.bfloat16)
+    # plant exact ties: 1 + 2^-8 lies halfway between the bf16 neighbours 1 and 1 + 2^-7
+    Yp[0, :4] = torch.tensor([1.0, 1.0078125, -1.0, 3.0]).to(torch.bfloat16)
+    Yp[1, :4] = torch.tensor([2.0 ** -8, 2.0 ** -8, -(2.0 ** -8), 2.0 ** -7]).to(torch.bfloat16)
+    w = torch.ones((T, K))
+    rowp = torch.arange(T * K, dtype=torch.int32)
+    out = moe.moe_combine(Yp.cuda(), rowp.cuda(), w.cuda(), None, None)
+    ref = (Yp[0::2].float() + Yp[1::2].float()).to(torch.bfloat16)
+    assert torch.equal(out.cpu().view(torch.int16), ref.view(torch.int16))
+
+
 def test_stateless_and_deterministic(moe):
     wl = skewed_workload(T=400, H=128, E=12, K=4, I=128, Is=128, seed=22)
     a = run_layer(moe, wl, groups=workloads.partition(12, 5))
