@@ -183,11 +183,14 @@ def main() -> int:
 
     def layer_step(x, w, events=None):
         sh = (w["Wsg"], w["Wsu"], w["Wsd"], w["wgate"]) if s.Is > 0 else None
-        if overlap and events is None:       # shared expert (depends on x only) on the second stream
-            main = torch.cuda.current_stream()
-            side_stream.wait_stream(main)
-            with torch.cuda.stream(side_stream):
-                moe.moe_shared_forward(x, *sh, buf.S, buf.sg, buf.workspace_shared, args.shared_policy)
+        if overlap and events is None:
+            # the shared expert depends on x only: it forks off here to the second stream.  The routed
+            # path is enqueued first and stays on the stream that also runs the aggregation, so that
+            # the step's critical path (gating -> ... -> aggregation) never waits for a signal from
+            # another hardware queue (measured: about 10 us each at the fork and at the join); the
+            # short side branch pays them instead
+            fork = torch.cuda.Event()
+            fork.record()
         route(x, w)
         moe.moe_permute(buf.topk_ids, x, s.E, buf.expert_offsets, buf.src_of_row, buf.row_of_pair, buf.Xp,
                         buf.workspace_permute, materialize=not fused)
@@ -196,6 +199,9 @@ def main() -> int:
             if sh is not None and not overlap:
                 moe.moe_shared_forward(x, *sh, buf.S, buf.sg, buf.workspace_shared, args.shared_policy)
             if overlap:
+                side_stream.wait_event(fork)
+                with torch.cuda.stream(side_stream):
+                    moe.moe_shared_forward(x, *sh, buf.S, buf.sg, buf.workspace_shared, args.shared_policy)
                 torch.cuda.current_stream().wait_stream(side_stream)
         else:
             # same kernels, launched one per call so that events can bracket each of them

@@ -308,11 +308,10 @@ def moe_layer_forward(x, Wr, bias, Wg, Wu, Wd, shared, K: int, renorm: bool,
     if buf is None:
         buf = LayerBuffers.allocate(T, H, E, K, I, Is, x.device)
     main = torch.cuda.current_stream()
+    fork = None
     if shared is not None and shared_stream is not None:
-        shared_stream.wait_stream(main)
-        with torch.cuda.stream(shared_stream):
-            moe_shared_forward(x, shared[0], shared[1], shared[2], shared[3], buf.S, buf.sg, buf.workspace_shared,
-                               shared_policy)
+        fork = torch.cuda.Event()     # the shared expert needs x only: its branch forks off here
+        fork.record(main)
     if tenant_rows is not None:
         for i, (a, b) in enumerate(tenant_rows):
             moe_route(x[a:b], Wr, None if bias is None else bias[i], K, renorm, buf.topk_ids[a:b], buf.topk_w[a:b])
@@ -330,6 +329,12 @@ def moe_layer_forward(x, Wr, bias, Wg, Wu, Wd, shared, K: int, renorm: bool,
         moe_shared_forward(x, shared[0], shared[1], shared[2], shared[3], buf.S, buf.sg, buf.workspace_shared,
                            shared_policy)
     if shared is not None and shared_stream is not None:
+        # enqueued after the routed path, so that in a captured graph the routed path shares its
+        # hardware queue with the aggregation and the step's critical path crosses no queue boundary
+        shared_stream.wait_event(fork)
+        with torch.cuda.stream(shared_stream):
+            moe_shared_forward(x, shared[0], shared[1], shared[2], shared[3], buf.S, buf.sg, buf.workspace_shared,
+                               shared_policy)
         main.wait_stream(shared_stream)
     moe_combine(buf.Yp, buf.row_of_pair, buf.topk_w, buf.S, buf.sg, buf.out)
     return buf
