@@ -139,6 +139,72 @@ __global__ __launch_bounds__(256) void permute_scatter_kernel(const int32_t* __r
   }
 }
 
+// Few pairs and no row copies (index arrays only): the whole sort in one workgroup of up to 16
+// waves, one pair per thread.  Same arithmetic as the two kernels above (counts per wave and
+// expert, sums over earlier waves, scan over experts, rank inside the wave), without the table in
+// global memory and with one launch instead of two: at decode sizes the launches are the cost.
+constexpr int PERM_SMALL_MAX = 1024;
+__global__ __launch_bounds__(PERM_SMALL_MAX) void permute_small_kernel(const int32_t* __restrict__ ids, int P, int E,
+                                                                       int32_t* __restrict__ offsets,
+                                                                       int32_t* __restrict__ src_of_row,
+                                                                       int32_t* __restrict__ row_of_pair) {
+  __shared__ int s_cnt[PERM_SMALL_MAX / 64][PERM_EMAX];   // pairs of expert e in wave w; then: in earlier waves
+  __shared__ int s_base[PERM_EMAX];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int nwaves = blockDim.x >> 6;
+  for (int i = tid; i < nwaves * PERM_EMAX; i += blockDim.x) (&s_cnt[0][0])[i] = 0;
+  __syncthreads();
+  const int p = tid;
+  const bool valid = p < P;
+  const int e = valid ? min(max(ids[p], 0), E - 1) : 0;
+  const unsigned long long match = match_expert(e, valid, bits_for(E));
+  const unsigned long long below = match & ((1ull << lane) - 1ull);
+  if (valid && below == 0ull) s_cnt[wave][e] = __popcll(match);
+  __syncthreads();
+  for (int x = tid; x < E; x += blockDim.x) {   // expert x: exclusive sums over the waves, total
+    int run = 0;
+    for (int w = 0; w < nwaves; ++w) {
+      const int c = s_cnt[w][x];
+      s_cnt[w][x] = run;
+      run += c;
+    }
+    s_base[x] = run;
+  }
+  __syncthreads();
+  if (wave == 0) {   // exclusive scan of the totals over experts, four experts per lane
+    int v[4], sum = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int x = lane * 4 + i;
+      v[i] = x < E ? s_base[x] : 0;
+      sum += v[i];
+    }
+    int incl = sum;
+#pragma unroll
+    for (int s = 1; s < 64; s <<= 1) {
+      const int o = __shfl_up(incl, s, WAVE);
+      if (lane >= s) incl += o;
+    }
+    int base = incl - sum;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int x = lane * 4 + i;
+      if (x < E) {
+        s_base[x] = base;
+        offsets[x] = base;
+      }
+      base += v[i];
+    }
+    if (lane == 63) offsets[E] = incl;
+  }
+  __syncthreads();
+  if (valid) {
+    const int row = s_base[e] + s_cnt[wave][e] + __popcll(below);
+    row_of_pair[p] = row;
+    src_of_row[row] = p;
+  }
+}
+
 // P == 0: every offset is zero.
 __global__ void permute_empty_kernel(int E, int32_t* __restrict__ offsets) {
   for (int e = threadIdx.x; e <= E; e += blockDim.x) offsets[e] = 0;
@@ -149,6 +215,11 @@ int launch_permute(const int32_t* ids, const void* x, int T, int H, int E, int K
   const int P = T * K;
   if (P == 0) {
     hipLaunchKernelGGL(permute_empty_kernel, dim3(1), dim3(256), 0, st, E, offsets);
+    return hipGetLastError() == hipSuccess ? 0 : -4;
+  }
+  if (Xp == nullptr && P <= PERM_SMALL_MAX) {
+    const int threads = ((P + 63) / 64) * 64;
+    hipLaunchKernelGGL(permute_small_kernel, dim3(1), dim3(threads), 0, st, ids, P, E, offsets, src_of_row, row_of_pair);
     return hipGetLastError() == hipSuccess ? 0 : -4;
   }
   int32_t* hist = static_cast<int32_t*>(workspace);

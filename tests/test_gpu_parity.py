@@ -148,7 +148,8 @@ def test_route_slices_equal_the_whole(moe):
 
 @pytest.mark.parametrize("T,H,E,K", [(16, 64, 8, 2), (128, 2048, 60, 4), (4096, 2048, 60, 4), (1, 64, 4, 4),
                                       (300, 128, 7, 3), (0, 64, 5, 2), (40000, 64, 256, 4), (9000, 64, 60, 16),
-                                      (777, 192, 130, 5)])
+                                      (777, 192, 130, 5), (256, 64, 256, 4), (255, 64, 5, 4), (64, 64, 60, 16),
+                                      (13, 64, 200, 1)])
 def test_permute_bit_exact(moe, oracle64, T, H, E, K):
     print(f"[case] permute T={T} H={H} E={E} K={K}", flush=True)
     rng = np.random.default_rng(T + 7 * E)
@@ -169,6 +170,13 @@ def test_permute_bit_exact(moe, oracle64, T, H, E, K):
     if T > 0:
         expect = x[torch.from_numpy(src_r.astype(np.int64)) // K]
         assert torch.equal(Xp.cpu().view(torch.int16), expect.view(torch.int16))
+    # index arrays only (few pairs take a single-workgroup kernel): same arrays
+    off2, src2, rowp2, none = moe.moe_permute(torch.from_numpy(ids).cuda(), x.cuda(), E, materialize=False)
+    torch.cuda.synchronize()
+    assert none is None
+    assert np.array_equal(off2.cpu().numpy(), off_r)
+    assert np.array_equal(rowp2.cpu().numpy(), rowp_r)
+    assert np.array_equal(src2.cpu().numpy(), src_r)
 
 
 # ------------------------------------------------------------------------------ expert blocks
