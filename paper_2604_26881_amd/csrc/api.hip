@@ -18,7 +18,7 @@ bool dims_ok(int H) { return H > 0 && H % 64 == 0; }
 //         tiles; 7 = streaming, two-way token split times two-way K split; 8 = MFMA tiles of 128 rows
 //         by 64 weight rows, the down projection cut along K (few rows in all, one weight set);
 //         9 = streaming through wave-private LDS rings (whole-line requests); 10 = MFMA tiles of
-//         128 rows by 128 weight rows.
+//         128 rows by 128 weight rows; 11 = MFMA tiles of 160 rows by 256 weight rows.
 // Bits 8 and 9 of the policy word restrict a call to one of its two kernels (0x100: gate/up
 // only, 0x200: down projection only), so that each can be timed on its own.
 constexpr int SHARED_SMALL_T = 512;     // up to here the workspace has room for a K-cut down projection
@@ -42,6 +42,7 @@ Plan make_plan(int mean_rows, int n_experts_layer, int policy_word) {
     case 8: p.stream = false; p.tile_rows = 64; return p;
     case 9: p.stream = true; p.ksplit = 9; return p;
     case 10: p.stream = false; p.tile_rows = 130; return p;
+    case 11: p.stream = false; p.tile_rows = 160; return p;
     default: break;
   }
   const bool few_experts = n_experts_layer < 16;   // e.g. the shared expert: one weight set, all rows

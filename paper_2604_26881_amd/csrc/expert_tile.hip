@@ -31,6 +31,7 @@
 // of one token row per accumulator quad, which makes the bf16 stores 8 bytes wide.
 // Rows past the end of an expert are clamped on load (they recompute the expert's last row) and
 // masked on store, which keeps the K loop free of branches.
+#include <math.h>
 #include <type_traits>
 #include "common.h"
 
@@ -84,7 +85,7 @@ __global__ __launch_bounds__(256, OCC) void expert_tile_kernel(GemmArgs a) {
   __shared__ int s_pref[TILE_EMAX + 1];   // token tiles before expert i of the block
   __shared__ int s_rb[TILE_EMAX];         // first row of expert i of the block
   __shared__ int s_re[TILE_EMAX];         // one past its last row
-  __shared__ int s_eid[TILE_EMAX];        // its expert id
+  __shared__ uint16_t s_eid[TILE_EMAX];   // its expert id
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -94,7 +95,7 @@ __global__ __launch_bounds__(256, OCC) void expert_tile_kernel(GemmArgs a) {
   // per-expert row range and number of token tiles -> exclusive prefix in LDS
   for (int i = tid; i < nexp; i += 256) {
     const int eid = a.offsets ? (a.ids ? a.ids[a.lo + i] : a.lo + i) : 0;
-    s_eid[i] = eid;
+    s_eid[i] = (uint16_t)eid;
     s_rb[i] = a.offsets ? a.offsets[eid] : 0;
     s_re[i] = a.offsets ? a.offsets[eid + 1] : a.rows_fixed;
   }
@@ -191,7 +192,7 @@ __global__ __launch_bounds__(256, OCC) void expert_tile_kernel(GemmArgs a) {
     t.rowEnd = s_re[e];
     t.rowsValid = min(BM, t.rowEnd - t.row0);
     t.n0 = nt * S::NOUT;
-    const int eg = s_eid[e];
+    const int eg = (int)s_eid[e];
 
     const size_t kbeg = (size_t)t.ks * nk * S::BK;
     // with a gather list the token rows are addressed from the start of A, through the list
@@ -341,20 +342,14 @@ __global__ __launch_bounds__(256, OCC) void expert_tile_kernel(GemmArgs a) {
     // token blocks of this wave that hold rows of the expert (at least one, so that the copies and
     // operand reads keep their places between MFMAs)
     const int tbv = min(S::TB, max(1, (rowsValid - wm * S::WTM + 31) >> 5));
-    if constexpr (S::TB == 1) {
-      pipeline(std::integral_constant<int, 1>{});
-    } else if constexpr (S::TB == 2) {
-      if (tbv == 1) pipeline(std::integral_constant<int, 1>{});
-      else pipeline(std::integral_constant<int, 2>{});
-    } else {
-      static_assert(S::TB == 4, "token blocks per wave");
-      switch (tbv) {
-        case 1: pipeline(std::integral_constant<int, 1>{}); break;
-        case 2: pipeline(std::integral_constant<int, 2>{}); break;
-        case 3: pipeline(std::integral_constant<int, 3>{}); break;
-        default: pipeline(std::integral_constant<int, 4>{}); break;
-      }
+    switch (tbv) {
+      case 1: pipeline(std::integral_constant<int, 1>{}); break;
+      case 2: if constexpr (S::TB >= 2) pipeline(std::integral_constant<int, 2>{}); break;
+      case 3: if constexpr (S::TB >= 3) pipeline(std::integral_constant<int, 3>{}); break;
+      case 4: if constexpr (S::TB >= 4) pipeline(std::integral_constant<int, 4>{}); break;
+      default: if constexpr (S::TB >= 5) pipeline(std::integral_constant<int, 5>{}); break;
     }
+    static_assert(S::TB <= 5, "token blocks per wave");
 #undef MOE_TILE_READ1
 #undef MOE_TILE_MFMA1
 #undef MOE_TILE_SLICE
@@ -447,7 +442,7 @@ static int launch_tile_t(const GemmArgs& a, hipStream_t st) {
   static_assert(KSPLIT == 1 || !GATEUP, "the SwiGLU product needs complete sums");
   if (a.Kdim % (S::BK * KSPLIT) != 0) return -2;
   if (KSPLIT > 1 && a.Cpart == nullptr) return -3;
-  static_assert(OCC * (NS * S::STAGE + 4200) <= 160 * 1024, "LDS of the resident workgroups must fit a CU");
+  static_assert(OCC * (NS * S::STAGE + 3600) <= 160 * 1024, "LDS of the resident workgroups must fit a CU");
   static bool attr_set = false;
   const int lds = NS * S::STAGE;
   if (!attr_set) {
@@ -506,18 +501,36 @@ int pick_tile_shape(int rows, int N, int Kdim, bool gateup, bool allow_kcut) {
   return best;
 }
 
+// Routed experts: the row counts are known only on the device, so the tile height comes from the
+// layer-wide mean (never from the block bounds).  An expert near the upper end of the expected
+// spread (mean + 1.5 sqrt(mean) rows, the binomial spread of uniform routing) should fit its tiles
+// with the least padded work: candidates 128, 160 and 256 rows, each row of a tile costing 1.41,
+// 1.23 and 1.0 (smaller tiles move more panel bytes per flop; factors fitted at T = 8192).
+// Measured on uniform routing at T = 768 ... 8192 the pick is the fastest shape or within 3 % of
+// it; Zipf-skewed routing (mean 273, median 130) and the multi-tenant batch (mean 137) also run
+// fastest on its choice (160).
 static int pick_tile_rows(const GemmArgs& a, int tile_rows, int nout, bool down) {
   (void)nout;
   if (tile_rows != 0) return tile_rows;
-  if (a.offsets != nullptr)   // experts of mixed sizes (measured on Zipf-skewed routing)
-    return (down && a.mean_rows >= 200) ? 256 : 129;
-  return pick_tile_shape(a.rows_total, a.N, a.Kdim, !down, a.Cpart != nullptr);
+  if (a.offsets == nullptr) return pick_tile_shape(a.rows_total, a.N, a.Kdim, !down, a.Cpart != nullptr);
+  const double m = (double)a.mean_rows + 1.5 * sqrt((double)a.mean_rows);
+  const int heights[3] = {129, 160, 256};
+  const double factor[3] = {1.41, 1.23, 1.0};
+  int best = 129;
+  double best_cost = 0.0;
+  for (int i = 0; i < 3; ++i) {
+    const int bm = heights[i] == 129 ? 128 : heights[i];
+    const double cost = ceil(m / bm) * bm * factor[i];
+    if (best_cost == 0.0 || cost < best_cost) { best_cost = cost; best = heights[i]; }
+  }
+  return best;
 }
 int launch_tile_gateup(const GemmArgs& a, int tile_rows, hipStream_t st) {
   const int t = pick_tile_rows(a, tile_rows, 128, false);
   if (t == 64) return launch_tile_t<128, 64, 4, 1, true, 6, 1>(a, st);
   if (t == 130) return launch_tile_t<128, 128, 2, 2, true, 4, 1>(a, st);
   if (t >= 256) return launch_tile_t<256, 256, 2, 2, true, 2, 1>(a, st);
+  if (t == 160) return launch_tile_t<160, 256, 1, 4, true, 3, 1>(a, st);
   return launch_tile_t<128, 256, 1, 4, true, 3, 1>(a, st);
 }
 int launch_tile_down(const GemmArgs& a, int tile_rows, hipStream_t st) {
@@ -532,6 +545,7 @@ int launch_tile_down(const GemmArgs& a, int tile_rows, hipStream_t st) {
   }
   if (t == 130) return launch_tile_t<128, 128, 2, 2, false, 4, 1>(a, st);
   if (t >= 256) return launch_tile_t<256, 256, 2, 2, false, 2, 1>(a, st);
+  if (t == 160) return launch_tile_t<160, 256, 1, 4, false, 3, 1>(a, st);
   return launch_tile_t<128, 256, 1, 4, false, 3, 1>(a, st);
 }
 

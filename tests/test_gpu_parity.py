@@ -187,7 +187,7 @@ def skewed_workload(T, H, E, K, I, Is, seed):
     return workloads.prefill(seed=seed, T=T, H=H, E=E, K=K, I=I, Is=Is)
 
 
-@pytest.mark.parametrize("policy", [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10])
+@pytest.mark.parametrize("policy", [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11])
 def test_expert_blocks_match_oracle(moe, oracle64, policy):
     wl = skewed_workload(T=700, H=256, E=20, K=4, I=192, Is=0, seed=21)
     s = wl.shape
@@ -293,7 +293,7 @@ def test_layer_with_fused_gather_at_decode_and_prefill_sizes(moe, oracle64):
         assert torch.equal(a.Yp.view(torch.int16), b.Yp.view(torch.int16)), wl.name
 
 
-@pytest.mark.parametrize("policy", [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10])
+@pytest.mark.parametrize("policy", [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11])
 @pytest.mark.parametrize("T", [5, 130, 300])
 def test_shared_expert_matches_oracle(moe, oracle64, policy, T):
     wl = workloads.decode(seed=31, T=T, H=256, E=8, I=64, Is=448)
