@@ -605,7 +605,8 @@ def test_stack_of_layers_teacher_forced(moe, oracle64, shape):
 
 # ------------------------------------------------------------------------------ launch modes
 
-def test_graph_replays_equal_eager(moe):
+@pytest.mark.parametrize("fused", [False, True])
+def test_graph_replays_equal_eager(moe, fused):
     # the whole layer captured once in a HIP graph (shared expert on a second stream inside it) and
     # replayed several times, with eager work and synchronisations in between: every replay must
     # reproduce the eager result bit for bit
@@ -620,12 +621,14 @@ def test_graph_replays_equal_eager(moe):
     warm = torch.cuda.Stream()
     warm.wait_stream(torch.cuda.current_stream())
     with torch.cuda.stream(warm):
-        moe.moe_layer_forward(wl.x, wl.Wr, None, wl.Wg, wl.Wu, wl.Wd, sh, s.K, s.renorm, buf=buf, shared_stream=side)
+        moe.moe_layer_forward(wl.x, wl.Wr, None, wl.Wg, wl.Wu, wl.Wd, sh, s.K, s.renorm, buf=buf, shared_stream=side,
+                              fused_gather=fused)
     torch.cuda.current_stream().wait_stream(warm)
     torch.cuda.synchronize()
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph):
-        moe.moe_layer_forward(wl.x, wl.Wr, None, wl.Wg, wl.Wu, wl.Wd, sh, s.K, s.renorm, buf=buf, shared_stream=side)
+        moe.moe_layer_forward(wl.x, wl.Wr, None, wl.Wg, wl.Wu, wl.Wd, sh, s.K, s.renorm, buf=buf, shared_stream=side,
+                              fused_gather=fused)
     for i in range(4):
         buf.out.fill_(float(i))               # eager work between the replays (a fill kernel, no memset node)
         buf.Yp.fill_(1.0)
