@@ -201,7 +201,9 @@ def main() -> int:
             if overlap:
                 side_stream.wait_event(fork)
                 with torch.cuda.stream(side_stream):
-                    moe.moe_shared_forward(x, *sh, buf.S, buf.sg, buf.workspace_shared, args.shared_policy)
+                    # 0x400: the shared expert's first kernel leaves room on the CUs for the gating and
+                    # permute kernels that run at the same time on the main stream
+                    moe.moe_shared_forward(x, *sh, buf.S, buf.sg, buf.workspace_shared, args.shared_policy | 0x400)
                 torch.cuda.current_stream().wait_stream(side_stream)
         else:
             # same kernels, launched one per call so that events can bracket each of them

@@ -160,6 +160,9 @@ int moe_residual_norm(const void* x, const void* y, int T, int H, float eps, voi
  * Adding 0x100 to policy runs only the first kernel of the call (gate/up projections and SwiGLU
  * into the workspace), adding 0x200 only the second (down projection from the workspace, and for
  * the shared expert the gate logit): the two halves of one call, so each can be timed alone.
+ * Adding 0x400 to the policy of moe_shared_forward_ex (automatic shapes) keeps its first kernel off
+ * the one tile shape that occupies every register of a CU, so that small kernels issued on other
+ * streams at the same time (gating, micro-batch construction) are not held up behind it.
  */
 int moe_expert_group_forward_ex(int group_lo, int group_hi, const void* Xp,
                                 const int32_t* expert_offsets, const void* Wg, const void* Wu,

@@ -333,8 +333,9 @@ def moe_layer_forward(x, Wr, bias, Wg, Wu, Wd, shared, K: int, renorm: bool,
         # hardware queue with the aggregation and the step's critical path crosses no queue boundary
         shared_stream.wait_event(fork)
         with torch.cuda.stream(shared_stream):
+            # 0x400: leave room on the CUs for the small kernels of the routed path running beside it
             moe_shared_forward(x, shared[0], shared[1], shared[2], shared[3], buf.S, buf.sg, buf.workspace_shared,
-                               shared_policy)
+                               shared_policy | 0x400)
         main.wait_stream(shared_stream)
     moe_combine(buf.Yp, buf.row_of_pair, buf.topk_w, buf.S, buf.sg, buf.out)
     return buf

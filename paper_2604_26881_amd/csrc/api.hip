@@ -20,7 +20,9 @@ bool dims_ok(int H) { return H > 0 && H % 64 == 0; }
 //         9 = streaming through wave-private LDS rings (whole-line requests); 10 = MFMA tiles of
 //         128 rows by 128 weight rows; 11 = MFMA tiles of 160 rows by 256 weight rows.
 // Bits 8 and 9 of the policy word restrict a call to one of its two kernels (0x100: gate/up
-// only, 0x200: down projection only), so that each can be timed on its own.
+// only, 0x200: down projection only), so that each can be timed on its own.  Bit 10 (0x400, shared
+// expert with automatic shapes): its first kernel takes no tile shape that fills a CU completely,
+// so that small kernels of other streams (gating, micro-batch construction) run beside it.
 constexpr int SHARED_SMALL_T = 512;     // up to here the workspace has room for a K-cut down projection
 constexpr int SHARED_KPARTS_MAX = 8;    // parts of its down projection along K
 
@@ -230,6 +232,7 @@ int moe_shared_forward_ex(const void* x, const void* Wsg, const void* Wsu, const
   GemmArgs dn = gu;
   dn.A = (const bf16_t*)workspace; dn.B0 = (const bf16_t*)Wsd; dn.B1 = nullptr; dn.C = (bf16_t*)S;
   dn.N = H; dn.Kdim = Is; dn.Cpart = part;
+  gu.leave_room = (policy >> 10) & 1;
   int rc = ffn_forward(gu, dn, plan, (hipStream_t)stream);
   if (rc != 0) return rc;
   if (wgate && plan.do_down) return launch_gate_dot(x, wgate, T, H, sg, (hipStream_t)stream);

@@ -82,6 +82,8 @@ struct GemmArgs {
   float* Cpart;        // fp32 partial outputs [parts, rows_total, N] of kernels that cut K, else unused
   const int32_t* gather;   // nullptr: row r of A is A[r]; else row r of A is A[gather[r] / gather_div]
   int gather_div;          // (the token rows themselves, addressed through src_of_row: no permuted copy)
+  int leave_room;          // 1: no tile shape that takes a whole CU (all registers of every SIMD): kernels of
+                           // other streams can then share the CUs with this one
 };
 
 int launch_route(const void* x, const void* Wr, const float* bias, int T, int H, int E, int K, int renorm,
@@ -96,7 +98,7 @@ int launch_gate_dot(const void* x, const void* wgate, int T, int H, float* sg, h
 int launch_tile_gateup(const GemmArgs& a, int tile_rows, hipStream_t st);
 int launch_tile_down(const GemmArgs& a, int tile_rows, hipStream_t st);
 int tile_down_ksplit(int Kdim);   // K parts of the down projection when tile_rows == 64
-int pick_tile_shape(int rows, int N, int Kdim, bool gateup, bool allow_kcut);   // one weight set, known rows
+int pick_tile_shape(int rows, int N, int Kdim, bool gateup, bool allow_kcut, bool leave_room);   // one weight set, known rows
 int launch_stream_gateup(const GemmArgs& a, int ksplit, hipStream_t st);
 int launch_stream_down(const GemmArgs& a, int ksplit, hipStream_t st);
 // Streaming kernels that stage the weights through wave-private LDS rings (whole-line requests).

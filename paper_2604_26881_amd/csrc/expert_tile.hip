@@ -478,7 +478,7 @@ static int launch_tile_t(const GemmArgs& a, hipStream_t st) {
 // from timing the four shapes at T = 128 ... 8192 on the Qwen shape; the K cut pays a reduction
 // pass over its fp32 partial sums.
 int tile_down_ksplit(int Kdim) { return Kdim % 512 == 0 ? 8 : Kdim % 256 == 0 ? 4 : Kdim % 128 == 0 ? 2 : 1; }
-int pick_tile_shape(int rows, int N, int Kdim, bool gateup, bool allow_kcut) {
+int pick_tile_shape(int rows, int N, int Kdim, bool gateup, bool allow_kcut, bool leave_room) {
   struct Cand { int code, bm, nout; double c; };
   const Cand cands[4] = {{256, 256, gateup ? 128 : 256, 1.0}, {129, 128, gateup ? 128 : 256, 1.1},
                          {130, 128, gateup ? 64 : 128, 1.42}, {64, 128, gateup ? 32 : 64, 1.77}};
@@ -488,6 +488,7 @@ int pick_tile_shape(int rows, int N, int Kdim, bool gateup, bool allow_kcut) {
   double best_cost = 0.0;
   for (const Cand& k : cands) {
     int parts = 1;
+    if (k.code == 256 && leave_room) continue;   // 256x256 holds all 512 registers of every SIMD
     if (k.code == 64) {
       if (!gateup && !allow_kcut) continue;   // 32 column tiles would leave most CUs idle
       if (!gateup) parts = tile_down_ksplit(Kdim);
@@ -512,7 +513,7 @@ int pick_tile_shape(int rows, int N, int Kdim, bool gateup, bool allow_kcut) {
 static int pick_tile_rows(const GemmArgs& a, int tile_rows, int nout, bool down) {
   (void)nout;
   if (tile_rows != 0) return tile_rows;
-  if (a.offsets == nullptr) return pick_tile_shape(a.rows_total, a.N, a.Kdim, !down, a.Cpart != nullptr);
+  if (a.offsets == nullptr) return pick_tile_shape(a.rows_total, a.N, a.Kdim, !down, a.Cpart != nullptr, a.leave_room != 0);
   const double m = (double)a.mean_rows + 1.5 * sqrt((double)a.mean_rows);
   const int heights[3] = {129, 160, 256};
   const double factor[3] = {1.41, 1.23, 1.0};
