@@ -105,7 +105,7 @@ def main() -> int:
     args = ap.parse_args()
 
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on ONE GPU; the layer forward has no multi-GPU path "
+        print("bench.py: this library runs on ONE GPU; the layer forward has no multi-GPU path "
               "(token batches would shard without any exchange). Run with --gpus 1.", file=sys.stderr)
         return 2
     if not torch.cuda.is_available():
