@@ -281,6 +281,32 @@ def test_blocks_given_as_id_lists_equal_blocks_given_as_ranges(moe, policy):
     assert np.array_equal(Yc.view(torch.int16).cpu().numpy()[mine], Ya.view(torch.int16).cpu().numpy()[mine])
 
 
+@pytest.mark.parametrize("gather", [False, True])
+def test_on_demand_resident_blocks_equal_fully_resident_weights(moe, gather):
+    # weights in pinned host memory, two block slots on the device for four blocks: every batch evicts
+    # and reloads blocks, and the rows must equal those of the ordinary call on resident weights bit for bit
+    wl = skewed_workload(T=300, H=256, E=12, K=3, I=128, Is=0, seed=31)
+    s = wl.shape
+    g = wl.to("cuda")
+    res = moe.ExpertResidency(wl.Wg, wl.Wu, wl.Wd, g=3, slots=2)
+    assert res.resident_bytes() == 2 * 3 * 3 * s.I * s.H * 2
+    ws = torch.empty(s.P * s.I * 2, dtype=torch.uint8, device="cuda")
+    for rep, shift in enumerate((0, 5, 0)):                      # three batches with different tokens
+        x = torch.roll(g.x, shifts=shift, dims=0).contiguous()
+        ids, w = moe.moe_route(x, g.Wr, g.bias, s.K, s.renorm)
+        off, src, rowp, Xp = moe.moe_permute(ids, x, s.E)
+        Ya = torch.full((s.P, s.H), 768.0, dtype=torch.bfloat16, device="cuda")
+        moe.moe_expert_group_forward(0, s.E, Xp, off, g.Wg, g.Wu, g.Wd, Ya, ws)
+        counts = torch.diff(off).cpu().tolist()
+        Yb = torch.full((s.P, s.H), 768.0, dtype=torch.bfloat16, device="cuda")
+        n = res.forward_active_blocks(counts, x if gather else Xp, src if gather else None, s.K, off, Yb, ws)
+        torch.cuda.synchronize()
+        assert n == sum(1 for lo, hi in res.blocks if sum(counts[lo:hi]) > 0)
+        assert torch.equal(Ya.view(torch.int16), Yb.view(torch.int16)), f"batch {rep}"
+    assert res.misses >= 4 and res.hits + res.misses == 3 * n
+    assert len(res.slot_of) == 2                                  # never more blocks resident than slots
+
+
 def test_layer_with_fused_gather_at_decode_and_prefill_sizes(moe, oracle64):
     for wl in (workloads.decode(), workloads.prefill()):     # the sizes the benchmark times
         s = wl.shape
