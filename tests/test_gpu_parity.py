@@ -529,6 +529,43 @@ def test_private_orchestrators_agree_with_the_shared_one(moe, oracle64):
         check_close(f64(shared_buf.out)[a:b], ref["out"], f"tenant {i}, shared orchestrator")
 
 
+@pytest.mark.parametrize("policy", [0, 5, 9])
+def test_many_experts_and_wide_top_k(moe, oracle64, policy):
+    # the limits of the interface: 256 experts, top-16 (the per-expert tables of the kernels are full)
+    wl = workloads.prefill(seed=43, T=300, H=128, E=256, K=16, I=64, Is=0)
+    s = wl.shape
+    d = wl.f32_numpy()
+    ref = oracle64.layer(d["x"], d["Wr"], d["bias"], d["Wg"], d["Wu"], d["Wd"], None, s.K, s.renorm)
+    g = wl.to("cuda")
+    buf = moe.moe_layer_forward(g.x, g.Wr, g.bias, g.Wg, g.Wu, g.Wd, None, s.K, s.renorm, policy=policy,
+                                groups=[(0, 100), (100, 256)], fused_gather=(policy != 5))
+    torch.cuda.synchronize()
+    assert np.array_equal(buf.topk_ids.cpu().numpy(), ref["ids"])
+    assert np.array_equal(buf.expert_offsets.cpu().numpy(), ref["offsets"])
+    assert np.array_equal(buf.row_of_pair.cpu().numpy(), ref["row_of_pair"])
+    check_close(f64(buf.Yp), ref["Yp"], f"Yp, 256 experts, policy {policy}")
+    check_close(f64(buf.out), ref["out"], f"layer output, 256 experts, policy {policy}")
+
+
+def test_large_prefill_batch_sampled_tokens(moe, oracle64):
+    # four times the benchmark's prefill batch: 65 536 (token, slot) pairs, several 256-row tiles per expert
+    wl = workloads.prefill(seed=47, T=16384)
+    s = wl.shape
+    g = wl.to("cuda")
+    buf = moe.moe_layer_forward(g.x, g.Wr, g.bias, g.Wg, g.Wu, g.Wd, gpu_shared(g), s.K, s.renorm, fused_gather=True)
+    torch.cuda.synchronize()
+    d = wl.f32_numpy()
+    tok = sample_tokens(s.T, 12, 9)
+    ref, ids_ref, w_ref = oracle64.token_forward(tok, d["x"], d["Wr"], d["bias"], d["Wg"], d["Wu"], d["Wd"], shared_of(d),
+                                                 s.K, s.renorm)
+    assert np.array_equal(buf.topk_ids.cpu().numpy()[tok], ids_ref)
+    check_close(f64(buf.out)[tok], ref, "large prefill batch, sampled tokens")
+    off = buf.expert_offsets.cpu().numpy()
+    assert off[0] == 0 and off[-1] == s.P and np.all(np.diff(off) >= 0)
+    rowp = buf.row_of_pair.cpu().numpy()
+    assert np.array_equal(np.sort(rowp), np.arange(s.P))          # a permutation of the rows
+
+
 def test_empty_and_degenerate_inputs(moe, oracle64):
     # every token to the same K experts: E - K experts are empty
     wl = workloads.decode(seed=41, T=70, H=128, E=16, I=64, Is=0)
