@@ -198,18 +198,28 @@ static int launch_route_t(const void* x, const void* Wr, const float* bias, int 
 }
 
 // Few tokens: one token per workgroup of 8 waves that split the experts, each wave takes its
-// experts in one batch (latency).  Many tokens: 4 waves with two tokens each, every wave walks all
-// experts in batches of 4 (throughput; measured 53 against 61 us at T = 4096 for the same waves
-// splitting the experts of two shared tokens).
+// experts in one batch (latency).  From 384 tokens: the same with 4 waves (19 against 22 us at
+// T = 512, and with one wave per SIMD the workgroup fits beside a 128-row GEMM tile of another
+// stream instead of waiting behind it).  From 1024 tokens: 4 waves with two tokens each, every
+// wave walks all experts in batches of 4 (throughput; 53 against 61 us at T = 4096 for the same
+// waves splitting the experts of two shared tokens).
 #define MOE_ROUTE_ARGS x, Wr, bias, T, H, E, K, renorm, ids, w, st
 int launch_route(const void* x, const void* Wr, const float* bias, int T, int H, int E, int K, int renorm,
                  int32_t* ids, float* w, hipStream_t st) {
   const int chunks = (H + 511) / 512;
-  const bool many = T >= 1024;
-  if (chunks <= 1) return many ? launch_route_t<1, 4, 4, 4, true>(MOE_ROUTE_ARGS) : launch_route_t<1, 1, 8, 8>(MOE_ROUTE_ARGS);
-  if (chunks <= 2) return many ? launch_route_t<2, 2, 4, 4, true>(MOE_ROUTE_ARGS) : launch_route_t<2, 1, 8, 8>(MOE_ROUTE_ARGS);
-  if (chunks <= 4) return many ? launch_route_t<4, 2, 4, 4, true>(MOE_ROUTE_ARGS) : launch_route_t<4, 1, 4, 8>(MOE_ROUTE_ARGS);
-  if (chunks <= 8) return many ? launch_route_t<8, 2, 2, 4, true>(MOE_ROUTE_ARGS) : launch_route_t<8, 1, 2, 8>(MOE_ROUTE_ARGS);
+  const bool many = T >= 1024, mid = T >= 384;
+  if (chunks <= 1)
+    return many ? launch_route_t<1, 4, 4, 4, true>(MOE_ROUTE_ARGS)
+                : (mid ? launch_route_t<1, 1, 8, 4>(MOE_ROUTE_ARGS) : launch_route_t<1, 1, 8, 8>(MOE_ROUTE_ARGS));
+  if (chunks <= 2)
+    return many ? launch_route_t<2, 2, 4, 4, true>(MOE_ROUTE_ARGS)
+                : (mid ? launch_route_t<2, 1, 8, 4>(MOE_ROUTE_ARGS) : launch_route_t<2, 1, 8, 8>(MOE_ROUTE_ARGS));
+  if (chunks <= 4)
+    return many ? launch_route_t<4, 2, 4, 4, true>(MOE_ROUTE_ARGS)
+                : (mid ? launch_route_t<4, 1, 4, 4>(MOE_ROUTE_ARGS) : launch_route_t<4, 1, 4, 8>(MOE_ROUTE_ARGS));
+  if (chunks <= 8)
+    return many ? launch_route_t<8, 2, 2, 4, true>(MOE_ROUTE_ARGS)
+                : (mid ? launch_route_t<8, 1, 2, 4>(MOE_ROUTE_ARGS) : launch_route_t<8, 1, 2, 8>(MOE_ROUTE_ARGS));
   if (chunks <= 16) return launch_route_t<16, 1, 1, 4>(MOE_ROUTE_ARGS);
   return -2;
 }

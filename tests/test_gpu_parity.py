@@ -67,7 +67,8 @@ ROUTE_CASES = [
     (4096, 2048, 60, 4, False, True), (2049, 1024, 60, 4, True, True), (33, 512, 256, 8, False, True),
     (5, 4096, 64, 16, True, False), (3, 8192, 7, 7, False, True), (1, 64, 1, 1, True, False),
     (70, 1536, 130, 6, False, True), (1030, 512, 60, 4, False, True), (1027, 4096, 32, 2, True, False),
-    (1025, 448, 200, 5, False, True),
+    (1025, 448, 200, 5, False, True), (500, 2048, 60, 4, False, True), (700, 1024, 33, 3, True, False),
+    (400, 512, 100, 2, False, True), (999, 4096, 16, 4, True, True),
 ]
 
 
