@@ -82,54 +82,67 @@ template <int BM, int BN, int WAVES_M, int WAVES_N, bool GATEUP, int NS, int OCC
 __global__ __launch_bounds__(256, OCC) void expert_tile_kernel(GemmArgs a) {
   using S = TileShape<BM, BN, WAVES_M, WAVES_N, GATEUP, NS>;
   extern __shared__ __align__(16) unsigned char smem[];
-  __shared__ int s_pref[TILE_EMAX + 1];   // token tiles before expert i of the block
+  // Experts come in two classes.  One with at least HEAVY_MIN token tiles reuses every weight panel
+  // that often out of L2 and is bound by the matrix pipes; one with fewer streams its weights from
+  // HBM for little arithmetic and is bound by memory.  Walking the experts in id order would run
+  // long stretches of one kind (all CUs waiting for HBM, then HBM idle); instead the token tiles
+  // of each class are listed separately (experts in order inside a class) and the walk draws
+  // locality groups from the two lists in proportion, so both kinds are in flight at any time.
+  constexpr int HEAVY_MIN = 3;
+  __shared__ int s_pref[2][TILE_EMAX];    // token tiles of the same class before expert i of the block
   __shared__ int s_rb[TILE_EMAX];         // first row of expert i of the block
-  __shared__ int s_re[TILE_EMAX];         // one past its last row
-  __shared__ uint16_t s_eid[TILE_EMAX];   // its expert id
+  __shared__ uint8_t s_eid[TILE_EMAX];    // its expert id (E <= 256)
+  __shared__ int s_total[2];              // token tiles per class
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave / WAVES_N, wn = wave % WAVES_N;
   const int nexp = a.offsets ? a.hi - a.lo : 1;
 
-  // per-expert row range and number of token tiles -> exclusive prefix in LDS
-  for (int i = tid; i < nexp; i += 256) {
-    const int eid = a.offsets ? (a.ids ? a.ids[a.lo + i] : a.lo + i) : 0;
-    s_eid[i] = (uint16_t)eid;
-    s_rb[i] = a.offsets ? a.offsets[eid] : 0;
-    s_re[i] = a.offsets ? a.offsets[eid + 1] : a.rows_fixed;
-  }
-  __syncthreads();
+  // per-expert row range and number of token tiles -> exclusive prefix per class in LDS
   if (wave == 0) {
-    int v[4], sum = 0;
+    int v[4], cnt[2] = {0, 0};
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int e = lane * 4 + i;
-      v[i] = e < nexp ? (s_re[e] - s_rb[e] + BM - 1) / BM : 0;
-      sum += v[i];
+      v[i] = 0;
+      if (e < nexp) {
+        const int eid = a.offsets ? (a.ids ? a.ids[a.lo + e] : a.lo + e) : 0;
+        const int rb = a.offsets ? a.offsets[eid] : 0;
+        const int re = a.offsets ? a.offsets[eid + 1] : a.rows_fixed;
+        s_eid[e] = (uint8_t)eid;
+        s_rb[e] = rb;
+        v[i] = (max(re - rb, 0) + BM - 1) / BM;
+      }
+      cnt[v[i] >= HEAVY_MIN] += v[i];
     }
-    int incl = sum;
 #pragma unroll
-    for (int s = 1; s < 64; s <<= 1) {
-      const int o = __shfl_up(incl, s, WAVE);
-      if (lane >= s) incl += o;
-    }
-    int base = incl - sum;
+    for (int c = 0; c < 2; ++c) {
+      int incl = cnt[c];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int e = lane * 4 + i;
-      if (e < nexp) s_pref[e] = base;
-      base += v[i];
+      for (int s = 1; s < 64; s <<= 1) {
+        const int o = __shfl_up(incl, s, WAVE);
+        if (lane >= s) incl += o;
+      }
+      int base = incl - cnt[c];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int e = lane * 4 + i;
+        if (e < nexp) s_pref[c][e] = base;
+        if ((v[i] >= HEAVY_MIN) == (c == 1)) base += v[i];
+      }
+      if (lane == 63) s_total[c] = incl;
     }
-    if (lane == 63) s_pref[nexp] = incl;
   }
   __syncthreads();
-  const int totalM = s_pref[nexp];
+  const int total0 = s_total[0], total1 = s_total[1];
+  const int grp0 = (total0 + S::GM - 1) / S::GM, grp1 = (total1 + S::GM - 1) / S::GM;   // locality groups per class
+  const int ngrp = grp0 + grp1;
   const int NT = (a.N + S::NOUT - 1) / S::NOUT;
   const int Kdim = a.Kdim;
   const int nk = Kdim / S::BK / KSPLIT;          // K steps of one work item (a tile, or a K part of it)
   const int groupTiles = S::GM * NT;
-  const int Lend = ((totalM + S::GM - 1) / S::GM) * groupTiles * KSPLIT;
+  const int Lend = ngrp * groupTiles * KSPLIT;
 
   const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
   // copy assignment of this lane inside an 8-row block: row lane/8, 16-byte slot lane%8; the slot
@@ -167,32 +180,37 @@ __global__ __launch_bounds__(256, OCC) void expert_tile_kernel(GemmArgs a) {
   int it = 0;
   auto next_tile = [&]() -> TileState {
     TileState t{};
-    int L = 0, mrow = 0, nt = 0;
+    int L = 0, mrow = 0, nt = 0, cls = 0;
     for (;; ++it) {
       L = xcd_walk ? ((it * 8 + (int)(blockIdx.x & 7)) * run + slot) : (it * G + (int)blockIdx.x);
       if (L >= Lend) { t.valid = false; return t; }
       const int Lt = KSPLIT > 1 ? L / KSPLIT : L;
       const int grp = Lt / groupTiles, rem = Lt - grp * groupTiles;
-      mrow = grp * S::GM + rem % S::GM;
+      // group grp of the merged walk: light groups are spread evenly between the heavy ones
+      const int before = (int)((long long)grp * grp0 / ngrp);          // light groups among the first grp
+      cls = (int)((long long)(grp + 1) * grp0 / ngrp) > before ? 0 : 1;
+      mrow = (cls == 0 ? before : grp - before) * S::GM + rem % S::GM;
       nt = rem / S::GM;
-      if (mrow < totalM) break;
+      if (mrow < (cls == 0 ? total0 : total1)) break;
     }
     ++it;
     t.valid = true;
     t.ks = KSPLIT > 1 ? L % KSPLIT : 0;   // K part of this work item
 
-    // expert of this token tile: last e with s_pref[e] <= mrow
+    // expert of this token tile: last e with s_pref[cls][e] <= mrow (an expert of the other class
+    // repeats its successor's prefix, so the last one is of this class)
     int elo = 0, ehi = nexp;
     while (ehi - elo > 1) {
       const int mid = (elo + ehi) >> 1;
-      if (s_pref[mid] <= mrow) elo = mid; else ehi = mid;
+      if (s_pref[cls][mid] <= mrow) elo = mid; else ehi = mid;
     }
-    const int e = elo;
-    t.row0 = s_rb[e] + (mrow - s_pref[e]) * BM;
-    t.rowEnd = s_re[e];
+    // (the same in every lane: readfirstlane keeps them in scalar registers)
+    const int e = __builtin_amdgcn_readfirstlane(elo);
+    const int eg = __builtin_amdgcn_readfirstlane((int)s_eid[e]);
+    t.row0 = __builtin_amdgcn_readfirstlane(s_rb[e] + (mrow - s_pref[cls][e]) * BM);
+    t.rowEnd = a.offsets ? a.offsets[eg + 1] : a.rows_fixed;
     t.rowsValid = min(BM, t.rowEnd - t.row0);
     t.n0 = nt * S::NOUT;
-    const int eg = (int)s_eid[e];
 
     const size_t kbeg = (size_t)t.ks * nk * S::BK;
     // with a gather list the token rows are addressed from the start of A, through the list

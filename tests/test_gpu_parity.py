@@ -137,6 +137,30 @@ def test_route_logits_bit_exact_through_cancelling_bias(moe, oracle64):
                 assert np.array_equal(ids_o, expect)
 
 
+def test_route_logits_bit_exact_in_the_many_token_kernel(moe, oracle64):
+    # The same check for batches of 1024 tokens and more, which take a kernel of their own (several
+    # logits folded at once, the last two fold steps done by the reader of the row sums): the batch
+    # is one token repeated, so every row must select ids 0..K-1 at weight 1/E.
+    g = torch.Generator().manual_seed(78)
+    for (T, H, E, K) in [(1030, 2048, 60, 4), (1024, 512, 256, 8), (1500, 4096, 33, 16), (1025, 960, 61, 3),
+                         (1100, 1536, 130, 6)]:
+        print(f"[case] many-token logits through bias T={T} H={H} E={E} K={K}", flush=True)
+        ex = torch.randint(-8, 9, (2, H), generator=g).float()
+        x2 = ((torch.randint(0, 2, (2, H), generator=g).float() * 2 - 1) * torch.pow(2.0, ex)
+              * (1 + torch.rand((2, H), generator=g))).to(torch.bfloat16)
+        Wr = (torch.randn((E, H), generator=g) * 0.05).to(torch.bfloat16)
+        _, _, L = oracle64.route(x2.float().numpy(), Wr.float().numpy(), None, K, False, want_logits=True)
+        expect = np.tile(np.arange(K, dtype=np.int32), (T, 1))
+        for t in range(2):
+            for sign in (1.0, -1.0):
+                bias = torch.from_numpy(-sign * L[t]).contiguous()
+                xr = x2[t:t + 1].repeat(T, 1).contiguous()
+                ids, w = moe.moe_route(xr.cuda(), (Wr * sign).to(torch.bfloat16).cuda(), bias.cuda(), K, False)
+                torch.cuda.synchronize()
+                assert np.array_equal(ids.cpu().numpy(), expect), (t, sign)
+                assert np.allclose(w.cpu().numpy(), 1.0 / E, rtol=1e-6)
+
+
 def test_route_slices_equal_the_whole(moe):
     wl = workloads.tenants(seed=3, n_tenants=4, T_per=64, I=64, Is=0).to("cuda")
     ids_all, w_all = moe.moe_route(wl.x, wl.Wr, wl.bias[1], 4, False)
