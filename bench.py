@@ -145,6 +145,8 @@ def main() -> int:
                          "its own expert subset)")
     ap.add_argument("--layers", type=int, default=24, help="layers of the stack workload")
     ap.add_argument("--group-size", type=int, default=0, help="experts per expert block (0: one block)")
+    ap.add_argument("--route-per-tenant", action="store_true",
+                    help="tenants/stack workloads: one gating launch per tenant slice instead of one for the batch")
     ap.add_argument("--policy", type=int, default=0)
     ap.add_argument("--shared-policy", type=int, default=0)
     ap.add_argument("--block-streams", type=int, default=1,
@@ -207,8 +209,12 @@ def main() -> int:
     groups = workloads.partition(s.E, args.group_size) if args.group_size > 0 else [(0, s.E)]
     buf = moe.LayerBuffers.allocate(s.T, s.H, s.E, s.K, s.I, s.Is)
 
+    seg = moe.segment_offsets(wl.tenant_rows, s.T, "cuda") if wl.tenant_rows is not None else None
+
     def route(x, w):
-        if wl.tenant_rows is not None:
+        if seg is not None and not args.route_per_tenant:   # one gating launch, one bias row per tenant slice
+            moe.moe_route_segments(x, w["Wr"], w["bias"], seg, s.K, s.renorm, buf.topk_ids, buf.topk_w)
+        elif wl.tenant_rows is not None:
             for i, (a, b) in enumerate(wl.tenant_rows):
                 moe.moe_route(x[a:b], w["Wr"], w["bias"][i], s.K, s.renorm, buf.topk_ids[a:b], buf.topk_w[a:b])
         else:

@@ -65,6 +65,20 @@ int moe_route(const void* x, const void* Wr, const float* bias, int T, int H, in
               int renorm, int32_t* topk_ids, float* topk_w, void* stream);
 
 /*
+ * Gating of a batch assembled from several tenants' requests by a shared orchestrator (Sec. 3:
+ * the Shared orchestrator serves all tenants and batches across them): the same computation as
+ * moe_route, with one bias row per segment of the batch.  Token t of segment s, seg_offsets[s] <= t
+ * < seg_offsets[s+1], is routed with bias_rows[s,:]; the result equals n_seg calls of moe_route on
+ * the slices, bit for bit, in one launch.
+ *   bias_rows [n_seg,E] fp32 (device); seg_offsets [n_seg+1] int32 (device), ascending, first 0,
+ *   last T (tokens at or past the last bound, if any, take the last row); 1 <= n_seg <= 4096.
+ * The bounds are read on the device and not validated; the other arguments as in moe_route.
+ */
+int moe_route_segments(const void* x, const void* Wr, const float* bias_rows, const int32_t* seg_offsets,
+                       int n_seg, int T, int H, int E, int K, int renorm, int32_t* topk_ids,
+                       float* topk_w, void* stream);
+
+/*
  * Micro-batch construction (Sec. 3: after gating the orchestrator builds micro-batched routing
  * requests; Sec. 4.1: all tokens routed to one expert block are consolidated into one batched
  * invocation).  A stable counting sort of the P pairs p = t*K + j by expert id:

@@ -16,7 +16,7 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB = None
 
-SYMBOLS = ["moe_status_string", "moe_route", "moe_permute", "moe_expert_group_forward",
+SYMBOLS = ["moe_status_string", "moe_route", "moe_route_segments", "moe_permute", "moe_expert_group_forward",
            "moe_expert_group_forward_ex", "moe_expert_group_forward_gather", "moe_expert_list_forward",
            "moe_shared_forward", "moe_shared_forward_ex", "moe_combine",
            "moe_permute_workspace_bytes", "moe_expert_workspace_bytes", "moe_shared_workspace_bytes",
@@ -45,6 +45,9 @@ def load() -> ctypes.CDLL:
     lib.moe_status_string.argtypes = [c_int]
     lib.moe_route.restype = c_int
     lib.moe_route.argtypes = [c_vp, c_vp, c_vp, c_int, c_int, c_int, c_int, c_int, c_vp, c_vp, c_vp]
+    lib.moe_route_segments.restype = c_int
+    lib.moe_route_segments.argtypes = [c_vp, c_vp, c_vp, c_vp, c_int, c_int, c_int, c_int, c_int, c_int, c_vp, c_vp,
+                                       c_vp]
     lib.moe_permute.restype = c_int
     lib.moe_permute.argtypes = [c_vp, c_vp, c_int, c_int, c_int, c_int, c_vp, c_vp, c_vp, c_vp, c_vp, c_sz, c_vp]
     lib.moe_expert_group_forward.restype = c_int
@@ -116,6 +119,40 @@ def moe_route(x, Wr, bias, K: int, renorm: bool, topk_ids=None, topk_w=None):
                           _ptr(topk_ids, torch.int32, "topk_ids"), _ptr(topk_w, torch.float32, "topk_w"), _stream())
     _check(rc, "moe_route")
     return topk_ids, topk_w
+
+
+def moe_route_segments(x, Wr, bias_rows, seg_offsets, K: int, renorm: bool, topk_ids=None, topk_w=None):
+    """bias_rows [n_seg, E] fp32, seg_offsets [n_seg + 1] int32, both on the device: token t of
+    segment s is routed with bias_rows[s] (one launch for a batch assembled from several tenants)."""
+    T, H = x.shape
+    E = Wr.shape[0]
+    n_seg = bias_rows.shape[0]
+    if bias_rows.shape != (n_seg, E) or seg_offsets.numel() != n_seg + 1:
+        raise MoeError("moe_route_segments: bias_rows must be [n_seg, E] and seg_offsets [n_seg + 1]")
+    if topk_ids is None:
+        topk_ids = torch.empty((T, K), dtype=torch.int32, device=x.device)
+    if topk_w is None:
+        topk_w = torch.empty((T, K), dtype=torch.float32, device=x.device)
+    rc = load().moe_route_segments(_ptr(x, torch.bfloat16, "x"), _ptr(Wr, torch.bfloat16, "Wr"),
+                                   _ptr(bias_rows, torch.float32, "bias_rows"),
+                                   _ptr(seg_offsets, torch.int32, "seg_offsets"), n_seg, T, H, E, K,
+                                   int(bool(renorm)), _ptr(topk_ids, torch.int32, "topk_ids"),
+                                   _ptr(topk_w, torch.float32, "topk_w"), _stream())
+    _check(rc, "moe_route_segments")
+    return topk_ids, topk_w
+
+
+def segment_offsets(tenant_rows, T: int, device):
+    """Device array of segment bounds for moe_route_segments, or None when the tenants' row ranges
+    are not the consecutive slices [0, a1), [a1, a2), ... [.., T) of the batch."""
+    bounds = [0]
+    for a, b in tenant_rows:
+        if a != bounds[-1] or b < a:
+            return None
+        bounds.append(b)
+    if bounds[-1] != T:
+        return None
+    return torch.tensor(bounds, dtype=torch.int32, device=device)
 
 
 def moe_permute(topk_ids, x, E: int, expert_offsets=None, src_of_row=None, row_of_pair=None, Xp=None,
@@ -293,12 +330,14 @@ def moe_layer_forward(x, Wr, bias, Wg, Wu, Wd, shared, K: int, renorm: bool,
                       groups: Optional[Sequence[Tuple[int, int]]] = None, buf: Optional[LayerBuffers] = None,
                       tenant_rows: Optional[List[Tuple[int, int]]] = None, policy: int = 0,
                       shared_policy: int = 0, shared_stream: Optional[torch.cuda.Stream] = None,
-                      fused_gather: bool = False) -> LayerBuffers:
+                      fused_gather: bool = False, seg_offsets: Optional[torch.Tensor] = None) -> LayerBuffers:
     """One MoE layer in the paper's order: gating, micro-batch construction, one call per expert
     block, shared expert, aggregation.  Sequencing only; every step is a library call.
 
     shared: (Wsg, Wsu, Wsd, wgate) or None.  groups: expert blocks (lo, hi), default one block.
-    tenant_rows with a [n_tenants, E] bias: gating is called once per tenant slice.
+    tenant_rows with a [n_tenants, E] bias: one gating launch over the whole batch with one bias row
+    per tenant slice (seg_offsets: the slice bounds on the device, built here when not given; pass
+    it when the call is captured into a graph); slices that are not consecutive are gated one by one.
     shared_stream: run the shared expert on this stream, concurrently with gating, permutation and
     the routed blocks (it depends on x only); the aggregation waits for it.
     fused_gather: no permuted copy Xp; the block calls read x through src_of_row."""
@@ -312,7 +351,11 @@ def moe_layer_forward(x, Wr, bias, Wg, Wu, Wd, shared, K: int, renorm: bool,
     if shared is not None and shared_stream is not None:
         fork = torch.cuda.Event()     # the shared expert needs x only: its branch forks off here
         fork.record(main)
-    if tenant_rows is not None:
+    if tenant_rows is not None and bias is not None and seg_offsets is None:
+        seg_offsets = segment_offsets(tenant_rows, T, x.device)
+    if tenant_rows is not None and bias is not None and seg_offsets is not None:
+        moe_route_segments(x, Wr, bias, seg_offsets, K, renorm, buf.topk_ids, buf.topk_w)
+    elif tenant_rows is not None:
         for i, (a, b) in enumerate(tenant_rows):
             moe_route(x[a:b], Wr, None if bias is None else bias[i], K, renorm, buf.topk_ids[a:b], buf.topk_w[a:b])
     else:

@@ -151,7 +151,17 @@ int moe_route(const void* x, const void* Wr, const float* bias, int T, int H, in
   if (T < 0 || !dims_ok(H) || H > 8192 || E < 1 || E > 256 || K < 1 || K > 16 || K > E) return MOE_ERR_SHAPE;
   if (T == 0) return MOE_OK;
   if (!x || !Wr || !topk_ids || !topk_w) return MOE_ERR_NULL;
-  return launch_route(x, Wr, bias, T, H, E, K, renorm, topk_ids, topk_w, (hipStream_t)stream);
+  return launch_route(x, Wr, bias, nullptr, 0, T, H, E, K, renorm, topk_ids, topk_w, (hipStream_t)stream);
+}
+
+int moe_route_segments(const void* x, const void* Wr, const float* bias_rows, const int32_t* seg_offsets, int n_seg,
+                       int T, int H, int E, int K, int renorm, int32_t* topk_ids, float* topk_w, void* stream) {
+  if (T < 0 || !dims_ok(H) || H > 8192 || E < 1 || E > 256 || K < 1 || K > 16 || K > E) return MOE_ERR_SHAPE;
+  if (n_seg < 1 || n_seg > 4096) return MOE_ERR_SHAPE;
+  if (T == 0) return MOE_OK;
+  if (!x || !Wr || !bias_rows || !seg_offsets || !topk_ids || !topk_w) return MOE_ERR_NULL;
+  return launch_route(x, Wr, bias_rows, seg_offsets, n_seg, T, H, E, K, renorm, topk_ids, topk_w,
+                      (hipStream_t)stream);
 }
 
 int moe_permute(const int32_t* topk_ids, const void* x, int T, int H, int E, int K, int32_t* expert_offsets,

@@ -86,8 +86,9 @@ struct GemmArgs {
                            // other streams can then share the CUs with this one
 };
 
-int launch_route(const void* x, const void* Wr, const float* bias, int T, int H, int E, int K, int renorm,
-                 int32_t* ids, float* w, hipStream_t st);
+// bias [E] for all tokens (seg == nullptr), or bias [n_seg, E] with seg [n_seg + 1] segment bounds on the device
+int launch_route(const void* x, const void* Wr, const float* bias, const int32_t* seg, int n_seg, int T, int H, int E,
+                 int K, int renorm, int32_t* ids, float* w, hipStream_t st);
 int launch_permute(const int32_t* ids, const void* x, int T, int H, int E, int K, int32_t* offsets,
                    int32_t* src_of_row, int32_t* row_of_pair, void* Xp, void* workspace, hipStream_t st);
 int launch_combine(const void* Yp, const int32_t* row_of_pair, const float* w, const void* S, const float* sg,

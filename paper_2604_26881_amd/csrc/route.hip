@@ -130,13 +130,27 @@ __device__ __forceinline__ void softmax_topk(const float (&l)[4], int lane, int 
 
 // Few tokens: the NW waves of a workgroup share TOK tokens and split the experts.
 // FULL: H == 512 * C, so no lane is beyond the row and the loads carry no predicate.
+// Bias row of token t.  With segment bounds (seg[0] = 0 < ... , n_seg + 1 ascending entries) token
+// t of segment s (seg[s] <= t < seg[s+1]; tokens at or past seg[n_seg] count to the last one) takes
+// row s of bias [n_seg, E]; without them every token takes the one row.  t is uniform in the wave.
+__device__ __forceinline__ const float* bias_row(const float* bias, const int32_t* seg, int n_seg, int t, int E) {
+  if (bias == nullptr || seg == nullptr) return bias;
+  int s = 0;
+  while (s + 1 < n_seg && t >= seg[s + 1]) ++s;
+  return bias + (size_t)s * E;
+}
+
 template <int C, int TOK, int EB, int NW, bool FULL>
 __global__ __launch_bounds__(NW * 64) void route_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ Wr,
-                                                        const float* __restrict__ bias, int T, int H, int E, int K,
-                                                        int renorm, int32_t* __restrict__ ids, float* __restrict__ w) {
+                                                        const float* __restrict__ bias_rows,
+                                                        const int32_t* __restrict__ seg, int n_seg, int T, int H,
+                                                        int E, int K, int renorm, int32_t* __restrict__ ids,
+                                                        float* __restrict__ w) {
+  static_assert(TOK == 1, "one bias row per workgroup");
   __shared__ float s_logit[TOK][ROUTE_EMAX];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int t0 = blockIdx.x * TOK;
+  const float* bias = bias_row(bias_rows, seg, n_seg, t0, E);
 
   // token rows -> fp32 registers (zero beyond H or T; a zero product leaves a partial sum unchanged)
   float xf[TOK][C][8];
@@ -240,9 +254,10 @@ __global__ __launch_bounds__(NW * 64) void route_kernel(const bf16_t* __restrict
 // clamped copies of row E-1; their sums land in the padding and are never read).
 template <int C, int TOK, int EB, bool FULL>
 __global__ __launch_bounds__(256) void route_many_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ Wr,
-                                                         const float* __restrict__ bias, int T, int H, int E, int EP,
-                                                         int K, int renorm, int32_t* __restrict__ ids,
-                                                         float* __restrict__ w) {
+                                                         const float* __restrict__ bias_rows,
+                                                         const int32_t* __restrict__ seg, int n_seg, int T, int H,
+                                                         int E, int EP, int K, int renorm,
+                                                         int32_t* __restrict__ ids, float* __restrict__ w) {
   constexpr int NW = 4, WTOK = NW * TOK, NV = EB * TOK, NJ = NV / 4;
   extern __shared__ float4 s_rows[];   // [WTOK][EP] : row sums 0..3 of a logit
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -331,6 +346,7 @@ __global__ __launch_bounds__(256) void route_many_kernel(const bf16_t* __restric
   for (int tk = wave; tk < WTOK; tk += NW) {
     const int t = tbase + tk;
     if (t >= T) break;
+    const float* bias = bias_row(bias_rows, seg, n_seg, t, E);
     float l[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -347,19 +363,19 @@ __global__ __launch_bounds__(256) void route_many_kernel(const bf16_t* __restric
   }
 }
 
-#define MOE_ROUTE_PARAMS const void* x, const void* Wr, const float* bias, int T, int H, int E, int K, int renorm, \
-                         int32_t* ids, float* w, hipStream_t st
-#define MOE_ROUTE_ARGS x, Wr, bias, T, H, E, K, renorm, ids, w, st
+#define MOE_ROUTE_PARAMS const void* x, const void* Wr, const float* bias, const int32_t* seg, int n_seg, int T, int H, \
+                         int E, int K, int renorm, int32_t* ids, float* w, hipStream_t st
+#define MOE_ROUTE_ARGS x, Wr, bias, seg, n_seg, T, H, E, K, renorm, ids, w, st
 
 template <int C, int TOK, int EB, int NW>
 static int launch_route_t(MOE_ROUTE_PARAMS) {
   const int blocks = (T + TOK - 1) / TOK;
   if (H == 512 * C)
     hipLaunchKernelGGL((route_kernel<C, TOK, EB, NW, true>), dim3(blocks), dim3(NW * 64), 0, st, (const bf16_t*)x,
-                       (const bf16_t*)Wr, bias, T, H, E, K, renorm, ids, w);
+                       (const bf16_t*)Wr, bias, seg, n_seg, T, H, E, K, renorm, ids, w);
   else
     hipLaunchKernelGGL((route_kernel<C, TOK, EB, NW, false>), dim3(blocks), dim3(NW * 64), 0, st, (const bf16_t*)x,
-                       (const bf16_t*)Wr, bias, T, H, E, K, renorm, ids, w);
+                       (const bf16_t*)Wr, bias, seg, n_seg, T, H, E, K, renorm, ids, w);
   return hipGetLastError() == hipSuccess ? 0 : -4;
 }
 
@@ -371,10 +387,10 @@ static int launch_route_many(MOE_ROUTE_PARAMS) {
   const size_t lds = (size_t)WTOK * EP * sizeof(float4);   // at most 16 tokens * 256 experts * 16 B = 64 KiB
   if (H == 512 * C)
     hipLaunchKernelGGL((route_many_kernel<C, TOK, EB, true>), dim3(blocks), dim3(256), lds, st, (const bf16_t*)x,
-                       (const bf16_t*)Wr, bias, T, H, E, EP, K, renorm, ids, w);
+                       (const bf16_t*)Wr, bias, seg, n_seg, T, H, E, EP, K, renorm, ids, w);
   else
     hipLaunchKernelGGL((route_many_kernel<C, TOK, EB, false>), dim3(blocks), dim3(256), lds, st, (const bf16_t*)x,
-                       (const bf16_t*)Wr, bias, T, H, E, EP, K, renorm, ids, w);
+                       (const bf16_t*)Wr, bias, seg, n_seg, T, H, E, EP, K, renorm, ids, w);
   return hipGetLastError() == hipSuccess ? 0 : -4;
 }
 
@@ -392,7 +408,7 @@ int launch_route(MOE_ROUTE_PARAMS) {
     return many ? launch_route_many<2, 2, 4>(MOE_ROUTE_ARGS)
                 : (mid ? launch_route_t<2, 1, 8, 4>(MOE_ROUTE_ARGS) : launch_route_t<2, 1, 8, 8>(MOE_ROUTE_ARGS));
   if (chunks <= 4)
-    return many ? launch_route_many<4, 2, 4>(MOE_ROUTE_ARGS)
+    return many ? launch_route_many<4, 2, 2>(MOE_ROUTE_ARGS)
                 : (mid ? launch_route_t<4, 1, 4, 4>(MOE_ROUTE_ARGS) : launch_route_t<4, 1, 4, 8>(MOE_ROUTE_ARGS));
   if (chunks <= 8)
     return many ? launch_route_many<8, 2, 2>(MOE_ROUTE_ARGS)

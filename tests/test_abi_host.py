@@ -60,6 +60,13 @@ def test_bad_arguments_are_rejected_before_any_launch(lib):
     assert lib.moe_route(p, p, None, -1, 64, 8, 2, 0, p, p, None) == SHAPE
     assert lib.moe_route(None, p, None, 4, 64, 8, 2, 0, p, p, None) == NULL
     assert lib.moe_route(None, None, None, 0, 64, 8, 2, 0, None, None, None) == 0   # T = 0: no-op
+    # route, one bias row per segment
+    assert lib.moe_route_segments(p, p, p, p, 0, 4, 64, 8, 2, 0, p, p, None) == SHAPE       # no segment
+    assert lib.moe_route_segments(p, p, p, p, 5000, 4, 64, 8, 2, 0, p, p, None) == SHAPE
+    assert lib.moe_route_segments(p, p, p, p, 2, 4, 64, 8, 9, 0, p, p, None) == SHAPE       # K > E
+    assert lib.moe_route_segments(p, p, None, p, 2, 4, 64, 8, 2, 0, p, p, None) == NULL     # bias rows are required
+    assert lib.moe_route_segments(p, p, p, None, 2, 4, 64, 8, 2, 0, p, p, None) == NULL
+    assert lib.moe_route_segments(None, None, None, None, 1, 0, 64, 8, 2, 0, None, None, None) == 0
     # permute
     assert lib.moe_permute(p, p, 4, 64, 8, 2, None, p, p, p, p, 1 << 20, None) == NULL
     assert lib.moe_permute(p, p, 4, 64, 8, 2, p, p, p, p, p, 8, None) == WS
@@ -112,3 +119,11 @@ def test_balanced_blocks_partition_and_balance():
         loads = [sum(rows[e] for e in b) for b in blocks]
         assert max(loads) - min(loads) <= max(rows)          # greedy bound: spread at most one item
     assert balanced_blocks([5, 5, 5, 5], 2) == [[0, 2], [1, 3]]
+
+
+def test_segment_offsets_accepts_only_consecutive_slices():
+    from paper_2604_26881_amd import segment_offsets
+    assert segment_offsets([(0, 3), (3, 3), (3, 10)], 10, "cpu").tolist() == [0, 3, 3, 10]
+    assert segment_offsets([(0, 3), (4, 10)], 10, "cpu") is None      # a gap
+    assert segment_offsets([(3, 10), (0, 3)], 10, "cpu") is None      # out of order
+    assert segment_offsets([(0, 3), (3, 9)], 10, "cpu") is None       # does not cover the batch

@@ -169,6 +169,39 @@ def test_route_slices_equal_the_whole(moe):
     assert torch.equal(ids_all[64:128], ids_s) and torch.equal(w_all[64:128], w_s)
 
 
+@pytest.mark.parametrize("bounds", [[0, 64, 128, 192, 256], [0, 1, 2, 300], [0, 700, 700, 1500, 2049],
+                                    [0, 512, 1024, 1536, 2048], [0, 5]])
+def test_route_segments_equal_one_call_per_slice(moe, oracle64, bounds):
+    # one bias row per segment of the batch, in one launch: the slices routed one by one are the
+    # reference (and the oracle on two of the slices); uneven and empty segments, both gating kernels
+    T, n = bounds[-1], len(bounds) - 1
+    print(f"[case] route segments {bounds}", flush=True)
+    g = torch.Generator().manual_seed(T + n)
+    H, E, K = 2048, 60, 4
+    x = torch.randn((T, H), generator=g).to(torch.bfloat16)
+    Wr = (torch.randn((E, H), generator=g) * 0.02).to(torch.bfloat16)
+    bias = torch.randn((n, E), generator=g) * 2.0
+    xg, Wg_, bg = x.cuda(), Wr.cuda(), bias.cuda()
+    seg = torch.tensor(bounds, dtype=torch.int32, device="cuda")
+    ids, w = moe.moe_route_segments(xg, Wg_, bg, seg, K, True)
+    torch.cuda.synchronize()
+    for i in range(n):
+        a, b = bounds[i], bounds[i + 1]
+        if a == b:
+            continue
+        ids_s, w_s = moe.moe_route(xg[a:b], Wg_, bg[i], K, True)
+        torch.cuda.synchronize()
+        assert torch.equal(ids[a:b], ids_s) and torch.equal(w[a:b], w_s), f"segment {i}"
+    for i in (0, n - 1):
+        a, b = bounds[i], min(bounds[i + 1], bounds[i] + 40)
+        if a == b:
+            continue
+        ids_ref, w_ref = oracle64.route(x[a:b].float().numpy(), Wr.float().numpy(), bias[i].numpy(), K, True)
+        assert np.array_equal(ids[a:b].cpu().numpy(), ids_ref)
+        assert np.allclose(w[a:b].cpu().numpy(), w_ref, rtol=2e-5, atol=1e-9)
+    assert moe.segment_offsets([(bounds[i], bounds[i + 1]) for i in range(n)], T, "cuda").tolist() == bounds
+
+
 # ------------------------------------------------------------------------------ permutation
 
 @pytest.mark.parametrize("T,H,E,K", [(16, 64, 8, 2), (128, 2048, 60, 4), (4096, 2048, 60, 4), (1, 64, 4, 4),
