@@ -351,7 +351,8 @@ def moe_layer_forward(x, Wr, bias, Wg, Wu, Wd, shared, K: int, renorm: bool,
     if shared is not None and shared_stream is not None:
         fork = torch.cuda.Event()     # the shared expert needs x only: its branch forks off here
         fork.record(main)
-    if tenant_rows is not None and bias is not None and seg_offsets is None:
+    if (tenant_rows is not None and bias is not None and seg_offsets is None and len(tenant_rows) > 1
+            and not torch.cuda.is_current_stream_capturing()):   # (a capture cannot take the host-to-device copy)
         seg_offsets = segment_offsets(tenant_rows, T, x.device)
     if tenant_rows is not None and bias is not None and seg_offsets is not None:
         moe_route_segments(x, Wr, bias, seg_offsets, K, renorm, buf.topk_ids, buf.topk_w)

@@ -761,6 +761,38 @@ def test_graph_replays_equal_eager(moe, fused):
         assert torch.equal(buf.out.view(torch.int16), ref_out.view(torch.int16)), f"replay {i}: out"
 
 
+@pytest.mark.parametrize("prepared", [True, False])
+def test_graph_capture_of_a_multi_tenant_layer(moe, prepared):
+    # tenants with their own router bias: captured with the segment bounds prepared beforehand (one
+    # gating launch) and without them (a capture cannot copy them to the device: one launch per
+    # tenant slice); both graphs must reproduce the eager result bit for bit
+    wl = workloads.tenants(seed=53, n_tenants=3, T_per=96, H=256, E=24, I=128, Is=0).to("cuda")
+    s = wl.shape
+    args = (wl.x, wl.Wr, wl.bias, wl.Wg, wl.Wu, wl.Wd, None, s.K, s.renorm)
+    eager = moe.moe_layer_forward(*args, tenant_rows=wl.tenant_rows)
+    torch.cuda.synchronize()
+    ref_out, ref_ids = eager.out.clone(), eager.topk_ids.clone()
+    seg = moe.segment_offsets(wl.tenant_rows, s.T, "cuda") if prepared else None
+    buf = moe.LayerBuffers.allocate(s.T, s.H, s.E, s.K, s.I, 0)
+    warm = torch.cuda.Stream()
+    warm.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(warm):
+        moe.moe_layer_forward(*args, tenant_rows=wl.tenant_rows, buf=buf, seg_offsets=seg)
+    torch.cuda.current_stream().wait_stream(warm)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        moe.moe_layer_forward(*args, tenant_rows=wl.tenant_rows, buf=buf, seg_offsets=seg)
+    for i in range(3):
+        buf.out.fill_(float(i))
+        buf.topk_ids.fill_(-1)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(buf.topk_ids, ref_ids), f"replay {i}: ids"
+        assert torch.equal(buf.out.view(torch.int16), ref_out.view(torch.int16)), f"replay {i}: out"
+
+
 def test_blocks_on_several_streams_equal_one_stream(moe):
     # expert blocks are stateless and touch disjoint rows: issued on different streams, in any order,
     # sharing one workspace, they give the rows one stream gives
