@@ -276,6 +276,43 @@ def test_expert_blocks_match_oracle(moe, oracle64, policy):
     check_close(f64(out), ref["out"], f"layer output policy {policy}")
 
 
+ROW_PATTERNS = {
+    # rows per expert; the tile walk lists experts with three or more token tiles apart from the others
+    "one expert has everything": [0, 0, 1900, 0, 0, 0],
+    "only small experts": [40, 1, 0, 130, 159, 160, 161, 33, 0, 319, 320, 5],
+    "large and small alternate": [700, 3, 481, 0, 90, 1000, 160, 480, 1, 0, 479, 64],
+    "empty at both ends": [0, 0, 500, 70, 0, 0],
+    "exact tile multiples": [128, 256, 320, 640, 160, 512],
+}
+
+
+@pytest.mark.parametrize("pattern", sorted(ROW_PATTERNS))
+@pytest.mark.parametrize("policy", [3, 4, 11, 10])
+def test_tile_kernels_on_extreme_row_distributions(moe, oracle64, pattern, policy):
+    # expert_offsets written directly (no gating): every tile shape must serve any mix of empty,
+    # tiny, tile-sized and very large experts, in range blocks cut at arbitrary places
+    counts = np.array(ROW_PATTERNS[pattern], dtype=np.int64)
+    E, H, I = len(counts), 128, 192
+    P = int(counts.sum())
+    print(f"[case] tile kernels, {pattern}, policy {policy}, P={P}", flush=True)
+    g = torch.Generator().manual_seed(P + policy)
+    Xp = torch.randn((P, H), generator=g).to(torch.bfloat16)
+    Wg = (torch.randn((E, I, H), generator=g) * 0.05).to(torch.bfloat16)
+    Wu = (torch.randn((E, I, H), generator=g) * 0.05).to(torch.bfloat16)
+    Wd = (torch.randn((E, H, I), generator=g) * 0.05).to(torch.bfloat16)
+    off = np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+    ref = oracle64.expert_group_forward(0, E, Xp.float().numpy(), off, Wg.float().numpy(), Wu.float().numpy(),
+                                        Wd.float().numpy())
+    offg = torch.from_numpy(off).cuda()
+    ws = torch.empty(int(moe.load().moe_expert_workspace_bytes(P, I)), dtype=torch.uint8, device="cuda")
+    Yp = torch.full((P, H), 768.0, dtype=torch.bfloat16, device="cuda")
+    cut = E // 3
+    for lo, hi in ((cut, E), (0, cut)):
+        moe.moe_expert_group_forward(lo, hi, Xp.cuda(), offg, Wg.cuda(), Wu.cuda(), Wd.cuda(), Yp, ws, policy)
+    torch.cuda.synchronize()
+    check_close(f64(Yp), ref, f"Yp, {pattern}, policy {policy}")
+
+
 @pytest.mark.parametrize("policy", [0, 1, 3, 4, 8, 9])
 def test_block_calls_reading_x_through_src_of_row_equal_the_permuted_copy(moe, oracle64, policy):
     # every kernel family: the gather folded into the first kernel gives the same bits as the copy Xp
