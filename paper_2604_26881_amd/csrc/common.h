@@ -44,6 +44,15 @@ __device__ __forceinline__ float wave_max(float v) {
   return v;
 }
 
+// Lanes l < 32 and l + 32 trade registers: afterwards a holds, in lanes 32-63, what b held in lanes
+// 0-31, and b holds, in lanes 0-31, what a held in lanes 32-63 (v_permlane32_swap); the other
+// halves keep their values.
+__device__ __forceinline__ void trade_halves(uint32_t& a, uint32_t& b) {
+  const auto r = __builtin_amdgcn_permlane32_swap(a, b, false, false);
+  a = r[0];
+  b = r[1];
+}
+
 // One 16-byte-per-lane copy from global memory straight into LDS (no registers in between):
 // lane l of the wave writes LDS bytes [lds + 16*l, +16) from global address base + voff.
 // The copy is asynchronous; it is counted by vmcnt like any other vector memory load.
