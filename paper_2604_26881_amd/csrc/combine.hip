@@ -30,16 +30,29 @@ __global__ __launch_bounds__(256) void combine_kernel(const bf16_t* __restrict__
     float acc[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) acc[i] = 0.0f;
-    for (int j = 0; j < K; ++j) {
-      const uint4 v = reinterpret_cast<const uint4*>(Yp + (size_t)s_row[j] * H)[c];
-      const float wj = s_w[j];
-      acc[0] = __builtin_fmaf(wj, bf16_lo(v.x), acc[0]); acc[1] = __builtin_fmaf(wj, bf16_hi(v.x), acc[1]);
-      acc[2] = __builtin_fmaf(wj, bf16_lo(v.y), acc[2]); acc[3] = __builtin_fmaf(wj, bf16_hi(v.y), acc[3]);
-      acc[4] = __builtin_fmaf(wj, bf16_lo(v.z), acc[4]); acc[5] = __builtin_fmaf(wj, bf16_hi(v.z), acc[5]);
-      acc[6] = __builtin_fmaf(wj, bf16_lo(v.w), acc[6]); acc[7] = __builtin_fmaf(wj, bf16_hi(v.w), acc[7]);
+    // the shared row and four expert rows at a time are requested before any of them is used
+    // (the sum still takes the rows in slot order)
+    uint4 vs = {0u, 0u, 0u, 0u};
+    if (S != nullptr) vs = reinterpret_cast<const uint4*>(S + (size_t)t * H)[c];
+    for (int j0 = 0; j0 < K; j0 += 4) {
+      uint4 vv[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+        if (j0 + u < K) vv[u] = reinterpret_cast<const uint4*>(Yp + (size_t)s_row[j0 + u] * H)[c];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        if (j0 + u < K) {
+          const uint4 v = vv[u];
+          const float wj = s_w[j0 + u];
+          acc[0] = __builtin_fmaf(wj, bf16_lo(v.x), acc[0]); acc[1] = __builtin_fmaf(wj, bf16_hi(v.x), acc[1]);
+          acc[2] = __builtin_fmaf(wj, bf16_lo(v.y), acc[2]); acc[3] = __builtin_fmaf(wj, bf16_hi(v.y), acc[3]);
+          acc[4] = __builtin_fmaf(wj, bf16_lo(v.z), acc[4]); acc[5] = __builtin_fmaf(wj, bf16_hi(v.z), acc[5]);
+          acc[6] = __builtin_fmaf(wj, bf16_lo(v.w), acc[6]); acc[7] = __builtin_fmaf(wj, bf16_hi(v.w), acc[7]);
+        }
+      }
     }
     if (S != nullptr) {
-      const uint4 v = reinterpret_cast<const uint4*>(S + (size_t)t * H)[c];
+      const uint4 v = vs;
       acc[0] = __builtin_fmaf(gate, bf16_lo(v.x), acc[0]); acc[1] = __builtin_fmaf(gate, bf16_hi(v.x), acc[1]);
       acc[2] = __builtin_fmaf(gate, bf16_lo(v.y), acc[2]); acc[3] = __builtin_fmaf(gate, bf16_hi(v.y), acc[3]);
       acc[4] = __builtin_fmaf(gate, bf16_lo(v.z), acc[4]); acc[5] = __builtin_fmaf(gate, bf16_hi(v.z), acc[5]);
