@@ -127,3 +127,12 @@ def test_segment_offsets_accepts_only_consecutive_slices():
     assert segment_offsets([(0, 3), (4, 10)], 10, "cpu") is None      # a gap
     assert segment_offsets([(3, 10), (0, 3)], 10, "cpu") is None      # out of order
     assert segment_offsets([(0, 3), (3, 9)], 10, "cpu") is None       # does not cover the batch
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in r.stderr + r.stdout
