@@ -17,7 +17,6 @@ replays unless --no-graph is given; both step times are in the JSON line.
 from __future__ import annotations
 
 import argparse
-import hashlib
 import json
 import os
 import sys
@@ -43,26 +42,17 @@ def layer_flops_per_token(s) -> int:
     return routed + shared + router + gate
 
 
-def csrc_sha256() -> str:
-    """Hash of the kernel sources: stored profiler counters are only valid for the kernels they were taken on."""
-    root = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2604_26881_amd", "csrc")
-    h = hashlib.sha256()
-    for name in sorted(os.listdir(root)):
-        with open(os.path.join(root, name), "rb") as f:
-            h.update(name.encode() + b"\0" + f.read())
-    return h.hexdigest()
-
-
-def measured_traffic(args, kernel: str):
+def measured_traffic(args, kernel: str, build_id: str):
     """HBM bytes per launch of `kernel` from stored rocprofv3 counter runs (FETCH_SIZE and WRITE_SIZE, each
     scaled by the same counter's reading for a plain copy of known size), or None when there is no
-    such record for this workload and launch configuration, or the kernel sources have changed since."""
+    such record for this workload and launch configuration, or the record was taken on another build
+    of the library than the one loaded (its id is the hash of the sources it was built from)."""
     path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "hbm_traffic.json")
     if args.policy != 0 or args.shared_policy != 0 or args.group_size != 0 or not os.path.exists(path):
         return None
     with open(path) as f:
         rec = json.load(f)
-    if rec.get("csrc_sha256") != csrc_sha256():
+    if rec.get("build_id") != build_id:
         return None
     e = rec.get("entries", {}).get(f"{args.workload}:{kernel}")
     return None if e is None else e["hbm_bytes_per_launch"]
@@ -171,6 +161,9 @@ def main() -> int:
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="before the timed steps, run three plain device copies of this many MiB (a kernel of "
                          "known HBM traffic, to scale profiler byte counters taken in the same run)")
+    ap.add_argument("--with-decode", type=int, default=1,
+                    help="prefill workload: 1 (default) also measures the decode batch (T = 128) in the same run and "
+                         "attaches it to the JSON line under \"decode\"; 0: prefill only")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     args = ap.parse_args()
@@ -189,6 +182,25 @@ def main() -> int:
     if args.workload == "residency":
         return run_residency(args, moe)
 
+    out = run_layer_workload(args, moe, cpu_baseline=not args.no_cpu_baseline)
+    if out is None:
+        return 2
+    if args.workload == "prefill" and args.with_decode:
+        # the weight-streaming regime in the same run: the decode batch (T = 128) through the same calls,
+        # measured the same way, its own roof (HBM) attached beside the prefill figures
+        dargs = argparse.Namespace(**vars(args))
+        dargs.workload = "decode"
+        dargs.steps, dargs.warmup = max(args.steps, 50), max(args.warmup, 10)
+        d = run_layer_workload(dargs, moe, cpu_baseline=False)
+        out["decode"] = {k: d[k] for k in ("value", "unit", "ms_per_step", "ms_per_step_eager", "ms_per_step_graph",
+                                           "steps", "warmup", "config", "layer_gbs", "layer_frac_of_hbm_peak",
+                                           "layer_bytes_algorithmic", "roofline", "kernels")}
+    print(json.dumps(out))
+    return 0
+
+
+def run_layer_workload(args, moe, cpu_baseline: bool):
+    """Measures one workload (prefill, decode, tenants or stack) and returns the record of its JSON line."""
     stack = args.workload == "stack"
     if stack:
         # 24 Qwen-shaped MoE layers (no attention), independent weights per layer drawn on the GPU
@@ -294,7 +306,9 @@ def main() -> int:
             ev[1][1].record()
             if sh is not None:
                 ev[2][0].record()
-                moe.moe_shared_forward(x, *sh, buf.S, buf.sg, buf.workspace_shared, args.shared_policy | GU)
+                # (with the same "leave room" bit as in the timed step, so the figure is for the shape the step runs)
+                moe.moe_shared_forward(x, *sh, buf.S, buf.sg, buf.workspace_shared,
+                                       args.shared_policy | GU | (0x400 if overlap else 0))
                 ev[2][1].record()
                 ev[3][0].record()
                 moe.moe_shared_forward(x, *sh, buf.S, buf.sg, buf.workspace_shared, args.shared_policy | DN)
@@ -305,7 +319,7 @@ def main() -> int:
     private = args.orchestrator == "private"
     if private and wl.tenant_rows is None:
         print("bench.py: --orchestrator private needs the tenants workload", file=sys.stderr)
-        return 2
+        return None
     if private:
         tbufs = [moe.LayerBuffers.allocate(b - a, s.H, s.E, s.K, s.I, s.Is) for a, b in wl.tenant_rows]
         tstreams = [torch.cuda.Stream() for _ in range(args.tenant_streams)] if args.tenant_streams > 1 else []
@@ -436,7 +450,7 @@ def main() -> int:
         achieved = alg_flops[dom] / launches / dur_s / 1e12
         roof = {"bound": "mfma", "achieved": achieved, "peak": PEAK_MFMA_BF16_TFLOPS, "unit": "TFLOP/s",
                 "frac": achieved / PEAK_MFMA_BF16_TFLOPS, "traffic": None}
-    roof["traffic"] = measured_traffic(args, dom)
+    roof["traffic"] = measured_traffic(args, dom, moe.build_id())
     roof.update({"kernel": dom, "launch_us": dur_s * 1e6, "launches_per_step": launches,
                  "algorithmic_flops_per_launch": alg_flops[dom] / launches,
                  "algorithmic_bytes_per_launch": alg_bytes[dom] / launches})
@@ -468,11 +482,11 @@ def main() -> int:
         "ms_per_step_eager": eager_ms, "ms_per_step_graph": graph_ms,
         "layer_tflops": layer_tflops, "layer_frac_of_mfma_peak": layer_tflops / PEAK_MFMA_BF16_TFLOPS,
         "layer_gbs": layer_bytes / (ms * 1e-3) / 1e9, "layer_frac_of_hbm_peak": layer_bytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
-        "flop_per_token": flop_tok, "roofline": roof, "kernels": kernels, "csrc_sha256": csrc_sha256(),
+        "flop_per_token": flop_tok, "layer_bytes_algorithmic": layer_bytes, "roofline": roof, "kernels": kernels, "build_id": moe.build_id(),
     }
 
     # ---- CPU baseline: the oracle, per-token definition, on a bounded sample of the same batch
-    if not args.no_cpu_baseline:
+    if cpu_baseline:
         import oracle
         orc = oracle.Oracle("f64")
         d = wl.f32_numpy()
@@ -494,8 +508,7 @@ def main() -> int:
         if stack:   # one layer was timed; the stack repeats it n_layers times per token
             out["cpu_baseline"]["value"] /= n_layers
             out["cpu_baseline"]["sample"] += f"; layer 0 only, divided by {n_layers} layers"
-    print(json.dumps(out))
-    return 0
+    return out
 
 
 if __name__ == "__main__":

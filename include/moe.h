@@ -19,8 +19,11 @@
  *  - Return value: MOE_OK (0), or a negative MOE_ERR_* code, in which case nothing was enqueued.
  *  - No hidden state: the result of a call is a function of its arguments alone (Sec. 3: expert
  *    blocks are stateless; the orchestrator keeps no cross-request state), so a call may be
- *    repeated, and calls on disjoint outputs may be issued in any order or on several streams.
- *  - Shape limits: H, I, Is multiples of 64; 1 <= K <= 16; K <= E <= 256; T*K < 2^31 / max(H,I).
+ *    repeated, and calls on disjoint outputs may be issued in any order, on several streams and
+ *    from several host threads (the library keeps nothing but a per-device note that a kernel's LDS
+ *    limit has been raised, set atomically).
+ *  - Shape limits: H, I, Is multiples of 64; 1 <= K <= 16; K <= E <= 256; T*K < 2^31 / max(H,I);
+ *    moe_route, moe_route_segments and moe_residual_norm: H <= 8192 (a token row lives in registers).
  *
  * Symbols: T tokens, H hidden size, E routed experts, K experts per token, P = T*K
  * (token, slot) pairs, I routed-expert intermediate size, Is shared-expert intermediate size.
@@ -43,6 +46,11 @@ extern "C" {
 
 /* Human-readable text for a status code (static storage, never NULL). */
 const char* moe_status_string(int status);
+
+/* Id of the sources this library was built from: SHA-256, as hex text, over the kernel sources and
+ * this header (static storage, never NULL; "unstamped" for a build that did not pass one).  Callers
+ * that keep measurements of the kernels (profiler counters) store it beside them. */
+const char* moe_build_id(void);
 
 /*
  * Gating (Sec. 2.1: the gating network selects the top-k experts per token; Sec. 3: it runs in
@@ -79,9 +87,10 @@ int moe_route_segments(const void* x, const void* Wr, const float* bias_rows, co
                        float* topk_w, void* stream);
 
 /*
- * Micro-batch construction (Sec. 3: after gating the orchestrator builds micro-batched routing
- * requests; Sec. 4.1: all tokens routed to one expert block are consolidated into one batched
- * invocation).  A stable counting sort of the P pairs p = t*K + j by expert id:
+ * Micro-batch construction (Sec. 3: after gating the orchestrator builds one routing request per
+ * expert block; Sec. 4.1 "token-level micro-batching": a block is invoked once per layer pass, on
+ * the batch of every token that gating sent to one of its experts).  A stable counting sort of the
+ * P pairs p = t*K + j by expert id:
  *   expert_offsets[e] .. expert_offsets[e+1]-1 are the rows of expert e (expert_offsets[E] = P);
  *   row_of_pair[p] = row that pair p lands on; src_of_row[r] = the pair on row r (its inverse);
  *   inside one expert the rows keep ascending p;  Xp[r,:] = x[src_of_row[r] / K, :].
@@ -112,6 +121,11 @@ int moe_permute(const int32_t* topk_ids, const void* x, int T, int H, int E, int
  *   Xp [P,H] bf16; expert_offsets [E+1] int32 ON THE DEVICE (read by the kernels);
  *   Wg, Wu [E,I,H] bf16; Wd [E,H,I] bf16 (the full tensors, not the block's slice);
  *   Yp [P,H] bf16.
+ * Guaranteed: of the three weight tensors a call dereferences only the slices of experts in
+ * [group_lo, group_hi) that have rows, i.e. bytes [e*I*H*2, (e+1)*I*H*2) past each base pointer
+ * for those e.  A caller that keeps only a block's weights on the device (on-demand residency,
+ * Sec. 3) may therefore pass base pointers moved back by group_lo experts from a buffer holding
+ * just that block; the same holds for the gather and the id-list forms below.
  * workspace: moe_expert_workspace_bytes(P, I) bytes, holding h (bf16 [P,I]).  Blocks that run
  * concurrently may share one workspace: each touches only its own rows.
  */
@@ -159,16 +173,13 @@ int moe_residual_norm(const void* x, const void* y, int T, int H, float eps, voi
 
 /*
  * The same two calls with the kernel shape picked by the caller instead of by the library
- * (measurement and tuning).  policy: 0 = automatic (what the plain calls use); 1 = weight-streaming
- * kernels, one 16-row weight block per wave; 2 = weight-streaming kernels with K split over the 4
- * waves of a workgroup; 3 and 5 = MFMA tiles of 128 token rows; 4 = MFMA tiles of 256 token
- * rows; 6 = weight-streaming kernels, the 4 waves share a weight block and split the token rows;
- * 7 = weight-streaming kernels, two-way token split times two-way K split; 8 = MFMA tiles of 128
- * token rows by 64 weight rows (for the shared expert, whose workspace has room for them, the down
- * projection is cut into up to 8 parts along K whose fp32 partial sums a second kernel adds in
- * ascending order; with policy 8 and T > 512 the shared call needs the workspace of
- * moe_shared_workspace_bytes plus 8*T*H*4 bytes); 9 = weight-streaming kernels that stage the
- * weights through wave-private LDS rings; 10 = MFMA tiles of 128 token rows by 128 weight rows.
+ * (measurement and tuning).  policy: 0 = automatic (what the plain calls use); 3 and 5 = MFMA tiles
+ * of 128 token rows by 256 weight rows; 4 = 256 by 256; 8 = 128 by 64 (for the shared expert, whose
+ * workspace has room for them, the down projection is cut into up to 8 parts along K whose fp32
+ * partial sums a second kernel adds in ascending order; with policy 8 and T > 512 the shared call
+ * needs the workspace of moe_shared_workspace_bytes plus 8*T*H*4 bytes); 9 = weight-streaming
+ * kernels that stage the weights through wave-private LDS rings (few rows per expert); 10 = MFMA
+ * tiles of 128 by 128; 11 = 160 by 256.  Any other number is refused with MOE_ERR_SHAPE.
  * Every policy computes the same function; results may differ in the last bf16 bit between
  * policies because the fp32 summation order differs.  Use one policy for all blocks of a layer.
  * Adding 0x100 to policy runs only the first kernel of the call (gate/up projections and SwiGLU

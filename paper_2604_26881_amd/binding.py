@@ -16,7 +16,7 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB = None
 
-SYMBOLS = ["moe_status_string", "moe_route", "moe_route_segments", "moe_permute", "moe_expert_group_forward",
+SYMBOLS = ["moe_status_string", "moe_build_id", "moe_route", "moe_route_segments", "moe_permute", "moe_expert_group_forward",
            "moe_expert_group_forward_ex", "moe_expert_group_forward_gather", "moe_expert_list_forward",
            "moe_shared_forward", "moe_shared_forward_ex", "moe_combine",
            "moe_permute_workspace_bytes", "moe_expert_workspace_bytes", "moe_shared_workspace_bytes",
@@ -32,15 +32,23 @@ def lib_path() -> str:
 
 
 def load() -> ctypes.CDLL:
-    """Load the built library (building it first only if it does not exist)."""
+    """Load the built library (building it first only if it does not exist).  A library that was built
+    from other sources than the ones beside it is refused: its results and timings would be
+    attributed to kernels that are not the ones running."""
     global _LIB
     if _LIB is not None:
         return _LIB
+    from . import build as _build
     if not os.path.exists(lib_path()):
-        from . import build as _build
         _build.build()
     lib = ctypes.CDLL(lib_path())
     c_int, c_vp, c_sz = ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t
+    lib.moe_build_id.restype = ctypes.c_char_p
+    lib.moe_build_id.argtypes = []
+    built, here = lib.moe_build_id().decode(), _build.source_id()
+    if built != here:
+        raise MoeError(f"{lib_path()} was built from other sources (library {built[:12]}, sources {here[:12]}): "
+                       "rebuild it with `python -m paper_2604_26881_amd.build`")
     lib.moe_status_string.restype = ctypes.c_char_p
     lib.moe_status_string.argtypes = [c_int]
     lib.moe_route.restype = c_int
@@ -80,6 +88,11 @@ def load() -> ctypes.CDLL:
     lib.moe_workspace_bytes.argtypes = [c_int] * 6
     _LIB = lib
     return lib
+
+
+def build_id() -> str:
+    """Id of the sources the loaded library was built from (see build.source_id)."""
+    return load().moe_build_id().decode()
 
 
 def _check(rc: int, what: str) -> None:
@@ -187,15 +200,17 @@ def moe_permute(topk_ids, x, E: int, expert_offsets=None, src_of_row=None, row_o
 
 def moe_expert_group_forward(group_lo: int, group_hi: int, Xp, expert_offsets, Wg, Wu, Wd, Yp, workspace,
                              policy: int = 0):
+    """policy 0 (default) is the plain call; any other value goes to moe_expert_group_forward_ex."""
     P, H = Xp.shape
     E, I, _ = Wg.shape
-    rc = load().moe_expert_group_forward_ex(int(group_lo), int(group_hi), _ptr(Xp, torch.bfloat16, "Xp"),
-                                            _ptr(expert_offsets, torch.int32, "expert_offsets"),
-                                            _ptr(Wg, torch.bfloat16, "Wg"), _ptr(Wu, torch.bfloat16, "Wu"),
-                                            _ptr(Wd, torch.bfloat16, "Wd"), P, H, E, I,
-                                            _ptr(Yp, torch.bfloat16, "Yp"), _ptr(workspace, None, "workspace"),
-                                            0 if workspace is None else workspace.numel() * workspace.element_size(),
-                                            int(policy), _stream())
+    args = (int(group_lo), int(group_hi), _ptr(Xp, torch.bfloat16, "Xp"),
+            _ptr(expert_offsets, torch.int32, "expert_offsets"), _ptr(Wg, torch.bfloat16, "Wg"),
+            _ptr(Wu, torch.bfloat16, "Wu"), _ptr(Wd, torch.bfloat16, "Wd"), P, H, E, I, _ptr(Yp, torch.bfloat16, "Yp"),
+            _ptr(workspace, None, "workspace"), 0 if workspace is None else workspace.numel() * workspace.element_size())
+    if int(policy) == 0:
+        rc = load().moe_expert_group_forward(*args, _stream())
+    else:
+        rc = load().moe_expert_group_forward_ex(*args, int(policy), _stream())
     _check(rc, "moe_expert_group_forward")
     return Yp
 
@@ -255,14 +270,17 @@ def balanced_blocks(rows_per_expert: Sequence[int], n_blocks: int) -> List[List[
 
 
 def moe_shared_forward(x, Wsg, Wsu, Wsd, wgate, S, sg, workspace, policy: int = 0):
+    """policy 0 (default) is the plain call; any other value goes to moe_shared_forward_ex."""
     T, H = x.shape
     Is = Wsg.shape[0]
-    rc = load().moe_shared_forward_ex(_ptr(x, torch.bfloat16, "x"), _ptr(Wsg, torch.bfloat16, "Wsg"),
-                                      _ptr(Wsu, torch.bfloat16, "Wsu"), _ptr(Wsd, torch.bfloat16, "Wsd"),
-                                      _ptr(wgate, torch.bfloat16, "wgate"), T, H, Is, _ptr(S, torch.bfloat16, "S"),
-                                      _ptr(sg, torch.float32, "sg"), _ptr(workspace, None, "workspace"),
-                                      0 if workspace is None else workspace.numel() * workspace.element_size(),
-                                      int(policy), _stream())
+    args = (_ptr(x, torch.bfloat16, "x"), _ptr(Wsg, torch.bfloat16, "Wsg"), _ptr(Wsu, torch.bfloat16, "Wsu"),
+            _ptr(Wsd, torch.bfloat16, "Wsd"), _ptr(wgate, torch.bfloat16, "wgate"), T, H, Is, _ptr(S, torch.bfloat16, "S"),
+            _ptr(sg, torch.float32, "sg"), _ptr(workspace, None, "workspace"),
+            0 if workspace is None else workspace.numel() * workspace.element_size())
+    if int(policy) == 0:
+        rc = load().moe_shared_forward(*args, _stream())
+    else:
+        rc = load().moe_shared_forward_ex(*args, int(policy), _stream())
     _check(rc, "moe_shared_forward")
     return S, sg
 

@@ -1,6 +1,7 @@
 """Builds libmoe_hip.so (the gfx950 kernels and the C entry points) in-tree with hipcc."""
 from __future__ import annotations
 
+import hashlib
 import os
 import subprocess
 import sys
@@ -10,16 +11,32 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libmoe_hip.so")
 OBJDIR = os.path.join(HERE, "_build")
-SOURCES = ["api.hip", "route.hip", "permute.hip", "combine.hip", "expert_tile.hip", "expert_stream.hip", "expert_stream_lds.hip"]
+SOURCES = ["api.hip", "route.hip", "permute.hip", "combine.hip", "expert_tile.hip", "expert_stream_lds.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          # packed-fp32 instructions are switched off for all device code
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 
+def source_id() -> str:
+    """SHA-256 over the library's sources (csrc/ and the C header), by file name and content.  The
+    build stamps it into the library (moe_build_id); the binding refuses a library whose stamp is not
+    the id of the sources beside it, and stored profiler counters carry the id of the kernels they
+    were taken on."""
+    h = hashlib.sha256()
+    files = [os.path.join(CSRC, n) for n in sorted(os.listdir(CSRC))]
+    files.append(os.path.join(os.path.dirname(HERE), "include", "moe.h"))
+    for path in files:
+        with open(path, "rb") as f:
+            h.update(os.path.basename(path).encode() + b"\0" + f.read())
+    return h.hexdigest()
+
+
 def _compile(src: str) -> str:
     obj = os.path.join(OBJDIR, os.path.splitext(src)[0] + ".o")
     cmd = [HIPCC, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+    if src == "api.hip":
+        cmd.append(f'-DMOE_BUILD_ID="{source_id()}"')
     r = subprocess.run(cmd, capture_output=True, text=True)
     err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
     if r.returncode != 0:

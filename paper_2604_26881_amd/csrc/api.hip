@@ -13,12 +13,10 @@ bool dims_ok(int H) { return H > 0 && H % 64 == 0; }
 
 // Which kernels serve an FFN with `mean_rows` expected rows per expert.  The choice uses only
 // layer-wide sizes (never the block bounds), so a row's result does not depend on the block cut.
-// policy: 0 = automatic; 1 = streaming, no K split; 2 = streaming, K split over 4 waves;
-//         3 and 5 = MFMA tiles of 128 rows; 4 = MFMA tiles of 256 rows; 6 = streaming, the waves split the token
-//         tiles; 7 = streaming, two-way token split times two-way K split; 8 = MFMA tiles of 128 rows
-//         by 64 weight rows, the down projection cut along K (few rows in all, one weight set);
-//         9 = streaming through wave-private LDS rings (whole-line requests); 10 = MFMA tiles of
-//         128 rows by 128 weight rows; 11 = MFMA tiles of 160 rows by 256 weight rows.
+// policy: 0 = automatic; 3 and 5 = MFMA tiles of 128 token rows by 256 weight rows; 4 = 256 by 256;
+//         8 = 128 by 64, the down projection cut along K (few rows in all, one weight set);
+//         9 = weight streaming through wave-private LDS rings (few rows per expert);
+//         10 = 128 by 128; 11 = 160 by 256.  Any other number is refused.
 // Bits 8 and 9 of the policy word restrict a call to one of its two kernels (0x100: gate/up
 // only, 0x200: down projection only), so that each can be timed on its own.  Bit 10 (0x400, shared
 // expert with automatic shapes): its first kernel takes no tile shape that fills a CU completely,
@@ -26,57 +24,40 @@ bool dims_ok(int H) { return H > 0 && H % 64 == 0; }
 constexpr int SHARED_SMALL_T = 512;     // up to here the workspace has room for a K-cut down projection
 constexpr int SHARED_KPARTS_MAX = 8;    // parts of its down projection along K
 
-struct Plan { bool stream; int ksplit; int tile_rows; bool do_gateup; bool do_down; };
+struct Plan { bool valid; bool stream; int tile_rows; bool do_gateup; bool do_down; };
 Plan make_plan(int mean_rows, int n_experts_layer, int policy_word) {
   Plan p{};
   const int phase = (policy_word >> 8) & 3;
   const int policy = policy_word & 0xff;
+  p.valid = (policy_word & ~0x7ff) == 0;
   p.do_gateup = phase == 0 || (phase & 1);
   p.do_down = phase == 0 || (phase & 2);
   switch (policy) {
-    case 1: p.stream = true; p.ksplit = 1; return p;
-    case 2: p.stream = true; p.ksplit = 4; return p;
-    case 6: p.stream = true; p.ksplit = 5; return p;
-    case 7: p.stream = true; p.ksplit = 6; return p;
-    case 3: p.stream = false; p.tile_rows = 128; return p;
-    case 4: p.stream = false; p.tile_rows = 256; return p;
-    case 5: p.stream = false; p.tile_rows = 129; return p;
-    case 8: p.stream = false; p.tile_rows = 64; return p;
-    case 9: p.stream = true; p.ksplit = 9; return p;
-    case 10: p.stream = false; p.tile_rows = 130; return p;
-    case 11: p.stream = false; p.tile_rows = 160; return p;
-    default: break;
+    case 0: break;
+    case 3: p.tile_rows = 128; return p;
+    case 4: p.tile_rows = 256; return p;
+    case 5: p.tile_rows = 129; return p;
+    case 8: p.tile_rows = 64; return p;
+    case 9: p.stream = true; return p;
+    case 10: p.tile_rows = 130; return p;
+    case 11: p.tile_rows = 160; return p;
+    default: p.valid = false; return p;
   }
-  const bool few_experts = n_experts_layer < 16;   // e.g. the shared expert: one weight set, all rows
-  if (few_experts) {
-    // measured with cold caches at the Qwen shape: K-split streaming wins up to 16 rows; beyond
-    // that MFMA tiles whose shape each kernel picks from its tile count (pick_tile_shape)
-    if (mean_rows <= 16) { p.stream = true; p.ksplit = 4; }
-    else { p.stream = false; p.tile_rows = 0; }
-    return p;
-  }
-  // routed experts, measured with cold caches at the Qwen shape: streaming through LDS rings wins
-  // up to a mean of about 26 rows per expert (T = 384), the MFMA tiles beyond
-  if (mean_rows <= 26) {
-    p.stream = true;
-    p.ksplit = 9;
-  } else {
-    p.stream = false;
-    p.tile_rows = 0;   // 256- or 128-row tiles, picked per kernel from the tile count
-  }
+  // One weight set on all rows (the shared expert): MFMA tiles whose shape each kernel picks from
+  // its tile count (pick_tile_shape).  Routed experts, measured with cold caches at the Qwen shape:
+  // streaming through LDS rings wins up to a mean of about 26 rows per expert (T = 384), the MFMA
+  // tiles beyond (their height picked from the layer-wide mean).
+  const bool few_experts = n_experts_layer < 16;
+  p.stream = !few_experts && mean_rows <= 26;
+  p.tile_rows = 0;
   return p;
 }
 
 int ffn_forward(const GemmArgs& gu, const GemmArgs& dn, const Plan& p, hipStream_t st) {
   int rc = 0;
-  if (p.stream && p.ksplit == 9) {
+  if (p.stream) {
     if (p.do_gateup && (rc = launch_stream_lds_gateup(gu, st)) != 0) return rc;
     if (p.do_down) rc = launch_stream_lds_down(dn, st);
-    return rc;
-  }
-  if (p.stream) {
-    if (p.do_gateup && (rc = launch_stream_gateup(gu, p.ksplit, st)) != 0) return rc;
-    if (p.do_down) rc = launch_stream_down(dn, p.ksplit, st);
     return rc;
   }
   if (p.do_gateup && (rc = launch_tile_gateup(gu, p.tile_rows, st)) != 0) return rc;
@@ -97,6 +78,7 @@ int expert_group_forward_impl(int group_lo, int group_hi, const int32_t* ids, co
   if (workspace_bytes < (size_t)P * (size_t)I * 2) return MOE_ERR_WORKSPACE;   // h, bf16 [P,I]
   const int mean_rows = (P + E - 1) / E;
   const Plan plan = make_plan(mean_rows, E, policy);
+  if (!plan.valid) return MOE_ERR_SHAPE;
   GemmArgs gu{};
   gu.A = (const bf16_t*)A; gu.B0 = (const bf16_t*)Wg; gu.B1 = (const bf16_t*)Wu; gu.C = (bf16_t*)workspace;
   gu.offsets = expert_offsets; gu.lo = group_lo; gu.hi = group_hi; gu.ids = ids; gu.rows_fixed = 0; gu.rows_total = P;
@@ -109,7 +91,13 @@ int expert_group_forward_impl(int group_lo, int group_hi, const int32_t* ids, co
 }
 }  // namespace
 
+#ifndef MOE_BUILD_ID
+#define MOE_BUILD_ID "unstamped"
+#endif
+
 extern "C" {
+
+const char* moe_build_id(void) { return MOE_BUILD_ID; }
 
 const char* moe_status_string(int status) {
   switch (status) {
@@ -223,6 +211,7 @@ int moe_shared_forward_ex(const void* x, const void* Wsg, const void* Wsu, const
   if (wgate && !sg) return MOE_ERR_NULL;
   if (workspace_bytes < (size_t)T * (size_t)Is * 2) return MOE_ERR_WORKSPACE;   // h, bf16 [T,Is]
   const Plan plan = make_plan(T, 1, policy);
+  if (!plan.valid) return MOE_ERR_SHAPE;
   const size_t h_bytes = align256((size_t)T * (size_t)Is * 2);
   const size_t part_bytes = (size_t)tile_down_ksplit(Is) * (size_t)T * (size_t)H * 4;
   float* part = nullptr;

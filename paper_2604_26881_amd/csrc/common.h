@@ -109,8 +109,6 @@ int launch_tile_gateup(const GemmArgs& a, int tile_rows, hipStream_t st);
 int launch_tile_down(const GemmArgs& a, int tile_rows, hipStream_t st);
 int tile_down_ksplit(int Kdim);   // K parts of the down projection when tile_rows == 64
 int pick_tile_shape(int rows, int N, int Kdim, bool gateup, bool allow_kcut, bool leave_room);   // one weight set, known rows
-int launch_stream_gateup(const GemmArgs& a, int ksplit, hipStream_t st);
-int launch_stream_down(const GemmArgs& a, int ksplit, hipStream_t st);
 // Streaming kernels that stage the weights through wave-private LDS rings (whole-line requests).
 int launch_stream_lds_gateup(const GemmArgs& a, hipStream_t st);
 int launch_stream_lds_down(const GemmArgs& a, hipStream_t st);

@@ -32,6 +32,7 @@
 // Rows past the end of an expert are clamped on load (they recompute the expert's last row) and
 // masked on store, which keeps the K loop free of branches.
 #include <math.h>
+#include <atomic>
 #include <type_traits>
 #include "common.h"
 
@@ -447,15 +448,12 @@ __global__ __launch_bounds__(256, OCC) void expert_tile_kernel(GemmArgs a) {
 #undef MOE_TILE_ISSUE
 }
 
+// Compute units of the current device (asked on every launch: nothing is cached across devices or threads).
 static int num_cus() {
-  static int cus = 0;
-  if (cus == 0) {
-    int dev = 0, n = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return 256;
-    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) return 256;
-    cus = n;
-  }
-  return cus;
+  int dev = 0, n = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return 256;
+  if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0) return 256;
+  return n;
 }
 
 // Sum of the KSPLIT fp32 partial outputs in ascending K part, rounded once to bf16.
@@ -483,11 +481,16 @@ static int launch_tile_t(const GemmArgs& a, hipStream_t st) {
   if (a.Kdim % (S::BK * KSPLIT) != 0) return -2;
   if (KSPLIT > 1 && a.Cpart == nullptr) return -3;
   static_assert(OCC * (NS * S::STAGE + 3600) <= 160 * 1024, "LDS of the resident workgroups must fit a CU");
-  static bool attr_set = false;
+  // The kernel's LDS limit is raised once per device: one bit per device id, set after the call has
+  // succeeded there (two threads may both make the call; it is idempotent).
+  static std::atomic<uint64_t> attr_done{0};
   const int lds = NS * S::STAGE;
-  if (!attr_set) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return -4;
+  const uint64_t bit = 1ull << (dev & 63);
+  if (dev >= 64 || !(attr_done.load(std::memory_order_acquire) & bit)) {
     if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess) return -4;
-    attr_set = true;
+    if (dev < 64) attr_done.fetch_or(bit, std::memory_order_release);
   }
   const int nexp = a.offsets ? a.hi - a.lo : 1;
   const int NT = (a.N + S::NOUT - 1) / S::NOUT;

@@ -1,5 +1,5 @@
-// Micro-batch construction (FaaSMoE Sec. 3 and Sec. 4.1: all tokens routed to one expert block
-// are consolidated into one batched invocation).  A stable counting sort of the P = T*K
+// Micro-batch construction (FaaSMoE Sec. 3; Sec. 4.1 "token-level micro-batching": each expert block
+// is invoked once, on the batch of every token gating sent to it).  A stable counting sort of the P = T*K
 // (token, slot) pairs by expert id, followed by a coalesced gather of the token rows.
 // No atomics anywhere, so the result is deterministic; every step runs on many CUs.
 //

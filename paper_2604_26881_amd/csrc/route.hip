@@ -135,8 +135,11 @@ __device__ __forceinline__ void softmax_topk(const float (&l)[4], int lane, int 
 // row s of bias [n_seg, E]; without them every token takes the one row.  t is uniform in the wave.
 __device__ __forceinline__ const float* bias_row(const float* bias, const int32_t* seg, int n_seg, int t, int E) {
   if (bias == nullptr || seg == nullptr) return bias;
-  int s = 0;
-  while (s + 1 < n_seg && t >= seg[s + 1]) ++s;
+  int s = 0, hi = n_seg - 1;       // last s with seg[s] <= t (s = 0 when there is none), by bisection
+  while (s < hi) {
+    const int mid = (s + hi + 1) >> 1;
+    if (t >= seg[mid]) s = mid; else hi = mid - 1;
+  }
   return bias + (size_t)s * E;
 }
 

@@ -32,6 +32,11 @@ def test_every_declared_symbol_is_exported(lib):
     assert sorted(binding.SYMBOLS) == names
 
 
+def test_library_carries_the_id_of_the_sources_beside_it(lib):
+    from paper_2604_26881_amd import binding, build
+    assert binding.build_id() == build.source_id() and len(build.source_id()) == 64
+
+
 def test_status_strings(lib):
     for code in (0, -1, -2, -3, -4, -99):
         s = lib.moe_status_string(code)
@@ -100,6 +105,15 @@ def test_bad_arguments_are_rejected_before_any_launch(lib):
     assert lib.moe_shared_forward(p, p, p, p, p, 4, 64, 96, p, p, p, 1 << 20, None) == SHAPE
     assert lib.moe_shared_forward(p, p, p, p, p, 4, 64, 128, p, None, p, 1 << 20, None) == NULL
     assert lib.moe_shared_forward(p, p, p, p, p, 4, 64, 128, p, p, p, 8, None) == WS
+    # kernel policies that do not exist (1, 2, 6 and 7 named kernels that have been removed) and stray bits
+    ex = lambda pol: lib.moe_expert_group_forward_ex(0, 8, p, p, p, p, p, 32, 64, 8, 128, p, p, 1 << 20, pol, None)
+    shx = lambda pol: lib.moe_shared_forward_ex(p, p, p, p, p, 4, 64, 128, p, p, p, 1 << 20, pol, None)
+    for pol in (1, 2, 6, 7, 12, 255, 0x800, 0x1003):
+        assert ex(pol) == SHAPE and shx(pol) == SHAPE, pol
+    # gating and the inter-layer step keep a token row in registers: H <= 8192
+    assert lib.moe_route(p, p, None, 4, 8256, 8, 2, 0, p, p, None) == SHAPE
+    assert lib.moe_route_segments(p, p, p, p, 2, 4, 8256, 8, 2, 0, p, p, None) == SHAPE
+    assert lib.moe_residual_norm(p, p, 4, 8256, ctypes.c_float(1e-6), p, None) == SHAPE
     # combine
     assert lib.moe_combine(p, p, p, p, None, 4, 64, 2, p, None) == NULL      # S without sg
     assert lib.moe_combine(p, p, p, None, None, 4, 64, 17, p, None) == SHAPE
