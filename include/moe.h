@@ -109,6 +109,23 @@ int moe_permute(const int32_t* topk_ids, const void* x, int T, int H, int E, int
                 void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * moe_permute for callers that cannot allocate device memory and have no workspace to pass: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The same sort
+ * with the same outputs, bit for bit; the table that moe_permute keeps in `workspace` lives in a
+ * buffer inside the library instead (a static device array of MOE_PERMUTE_STATIC_SCRATCH_BYTES
+ * that each GPU holds until the process ends).  The call allocates and frees nothing.
+ * Limit: ((T*K + 63) / 64) * E * 4 <= MOE_PERMUTE_STATIC_SCRATCH_BYTES (e.g. T*K <= 65 536 pairs at
+ * E = 256, 279 552 at E = 60); beyond it the call returns MOE_ERR_WORKSPACE and enqueues nothing.
+ * All calls on one GPU share that buffer: two calls that overlap in time on the same GPU (different
+ * streams) race on it and give undefined index arrays; calls ordered on one stream, or on different
+ * GPUs, are safe.  The buffer needs no clearing between calls.  Arguments as for moe_permute.
+ */
+#define MOE_PERMUTE_STATIC_SCRATCH_BYTES (1 << 20)
+int moe_permute_static(const int32_t* topk_ids, const void* x, int T, int H, int E, int K,
+                       int32_t* expert_offsets, int32_t* src_of_row, int32_t* row_of_pair, void* Xp,
+                       void* stream);
+
+/*
  * One expert-block invocation (Sec. 3: an expert block packages a configurable number of
  * experts behind one function and computes statelessly on the tokens assigned to it).
  * For every expert e in [group_lo, group_hi) and every row r of that expert:

@@ -16,7 +16,7 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB = None
 
-SYMBOLS = ["moe_status_string", "moe_build_id", "moe_route", "moe_route_segments", "moe_permute", "moe_expert_group_forward",
+SYMBOLS = ["moe_status_string", "moe_build_id", "moe_route", "moe_route_segments", "moe_permute", "moe_permute_static", "moe_expert_group_forward",
            "moe_expert_group_forward_ex", "moe_expert_group_forward_gather", "moe_expert_list_forward",
            "moe_shared_forward", "moe_shared_forward_ex", "moe_combine",
            "moe_permute_workspace_bytes", "moe_expert_workspace_bytes", "moe_shared_workspace_bytes",
@@ -58,6 +58,8 @@ def load() -> ctypes.CDLL:
                                        c_vp]
     lib.moe_permute.restype = c_int
     lib.moe_permute.argtypes = [c_vp, c_vp, c_int, c_int, c_int, c_int, c_vp, c_vp, c_vp, c_vp, c_vp, c_sz, c_vp]
+    lib.moe_permute_static.restype = c_int
+    lib.moe_permute_static.argtypes = [c_vp, c_vp, c_int, c_int, c_int, c_int, c_vp, c_vp, c_vp, c_vp, c_vp]
     lib.moe_expert_group_forward.restype = c_int
     lib.moe_expert_group_forward.argtypes = [c_int, c_int, c_vp, c_vp, c_vp, c_vp, c_vp, c_int, c_int, c_int, c_int,
                                              c_vp, c_vp, c_sz, c_vp]
@@ -195,6 +197,20 @@ def moe_permute(topk_ids, x, E: int, expert_offsets=None, src_of_row=None, row_o
                             _ptr(workspace, None, "workspace"), workspace.numel() * workspace.element_size(),
                             _stream())
     _check(rc, "moe_permute")
+    return expert_offsets, src_of_row, row_of_pair, Xp
+
+
+def moe_permute_static(topk_ids, x, E: int, expert_offsets, src_of_row, row_of_pair, Xp=None):
+    """moe_permute without a workspace and without any allocation: every output tensor is the caller's
+    (Xp None: index arrays only); the sort's table lives in a buffer inside the library."""
+    T, K = topk_ids.shape
+    H = x.shape[1]
+    rc = load().moe_permute_static(_ptr(topk_ids, torch.int32, "topk_ids"), _ptr(x, torch.bfloat16, "x"), T, H, E, K,
+                                   _ptr(expert_offsets, torch.int32, "expert_offsets"),
+                                   _ptr(src_of_row, torch.int32, "src_of_row"),
+                                   _ptr(row_of_pair, torch.int32, "row_of_pair"), _ptr(Xp, torch.bfloat16, "Xp"),
+                                   _stream())
+    _check(rc, "moe_permute_static")
     return expert_offsets, src_of_row, row_of_pair, Xp
 
 

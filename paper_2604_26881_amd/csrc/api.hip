@@ -1,5 +1,6 @@
 // C entry points of the MoE-layer library: argument checks and the choice of kernel shapes.
 // Semantics of every call are stated in include/moe.h.
+#include <atomic>
 #include "../../include/moe.h"
 #include "common.h"
 
@@ -91,6 +92,26 @@ int expert_group_forward_impl(int group_lo, int group_hi, const int32_t* ids, co
 }
 }  // namespace
 
+// Scratch memory of moe_permute_static: the per-chunk expert histogram of the counting sort, which
+// moe_permute keeps in the caller's workspace.  Every GPU the library runs on holds its own copy of
+// the array at its own address until the process ends.  In host code the array's name is not a
+// device address: the address on the current device is asked for once per device
+// (hipGetSymbolAddress) and kept; only that pointer is handed to kernels.
+static __device__ __align__(256) unsigned char scratch[MOE_PERMUTE_STATIC_SCRATCH_BYTES];
+static std::atomic<void*> scratch_on_device[64];   // by device id
+
+static int static_scratch(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return MOE_ERR_LAUNCH;
+  void* p = scratch_on_device[dev].load(std::memory_order_acquire);
+  if (p == nullptr) {
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) return MOE_ERR_LAUNCH;
+    scratch_on_device[dev].store(p, std::memory_order_release);
+  }
+  *out = p;
+  return MOE_OK;
+}
+
 #ifndef MOE_BUILD_ID
 #define MOE_BUILD_ID "unstamped"
 #endif
@@ -162,6 +183,23 @@ int moe_permute(const int32_t* topk_ids, const void* x, int T, int H, int E, int
   if (T > 0 && Xp && !x) return MOE_ERR_NULL;   // Xp == NULL: index arrays only, x is not read
   if (T > 0 && workspace_bytes < (((size_t)T * K + 63) / 64) * (size_t)E * 4) return MOE_ERR_WORKSPACE;
   return launch_permute(topk_ids, x, T, H, E, K, expert_offsets, src_of_row, row_of_pair, Xp, workspace,
+                        (hipStream_t)stream);
+}
+
+int moe_permute_static(const int32_t* topk_ids, const void* x, int T, int H, int E, int K, int32_t* expert_offsets,
+                       int32_t* src_of_row, int32_t* row_of_pair, void* Xp, void* stream) {
+  if (T < 0 || !dims_ok(H) || E < 1 || E > 256 || K < 1 || K > 16 || K > E) return MOE_ERR_SHAPE;
+  if ((long long)T * K * H >= (1ll << 31)) return MOE_ERR_SHAPE;
+  if (!expert_offsets) return MOE_ERR_NULL;
+  if (T > 0 && (!topk_ids || !src_of_row || !row_of_pair)) return MOE_ERR_NULL;
+  if (T > 0 && Xp && !x) return MOE_ERR_NULL;
+  if ((((size_t)T * K + 63) / 64) * (size_t)E * 4 > (size_t)MOE_PERMUTE_STATIC_SCRATCH_BYTES) return MOE_ERR_WORKSPACE;
+  void* table = nullptr;
+  const int rc = static_scratch(&table);
+  if (rc != MOE_OK) return rc;
+  // (the histogram kernel writes every table entry it later reads, so what an earlier call left
+  // behind needs no clearing)
+  return launch_permute(topk_ids, x, T, H, E, K, expert_offsets, src_of_row, row_of_pair, Xp, table,
                         (hipStream_t)stream);
 }
 
