@@ -144,6 +144,10 @@ def main() -> int:
     ap.add_argument("--fused-gather", type=int, default=1,
                     help="1 (default): no permuted copy of the tokens, the block calls read x through src_of_row; "
                          "0: moe_permute writes Xp and the block calls read it")
+    ap.add_argument("--fused-shared", type=int, default=0,
+                    help="1: the first block call also runs the shared experts (as Is / I experts of the routed size on "
+                         "every token) in the same two launches, where the library supports it (prefill-sized "
+                         "batches); 0 (default, measured faster): the shared expert is a call of its own")
     ap.add_argument("--balanced-blocks", type=int, default=0,
                     help="with --group-size g: form the E/g blocks by observed load (rows per expert of a warm-up "
                          "step, heaviest expert first to the lightest block) instead of as id ranges")
@@ -241,10 +245,21 @@ def run_layer_workload(args, moe, cpu_baseline: bool):
     block_streams = [torch.cuda.Stream() for _ in range(args.block_streams)] if args.block_streams > 1 else []
 
     fused = bool(args.fused_gather)
+    # the shared experts inside the first block call (needs the gather form and id-range blocks)
+    fshared = bool(args.fused_shared and fused and shared is not None and buf.S_parts is not None
+                   and not args.balanced_blocks and args.block_streams <= 1)
+    if fshared:
+        names = ["fused_gateup", "fused_down"]
+        overlap, side_stream = False, None
 
     block_lists = None     # per block an int32 device tensor of expert ids (load-balanced blocks)
 
     def block_call(x, w, lo, hi, policy):
+        if fshared and lo == groups[0][0]:
+            moe.moe_expert_group_forward_fused(lo, hi, x, buf.src_of_row, s.K, buf.expert_offsets, w["Wg"], w["Wu"],
+                                               w["Wd"], w["Wsg"], w["Wsu"], w["Wsd"], w["wgate"], buf.Yp, buf.S_parts,
+                                               buf.sg, buf.workspace_fused, policy)
+            return
         if block_lists is not None:
             moe.moe_expert_list_forward(block_lists[lo], x if fused else buf.Xp, buf.src_of_row if fused else None, s.K,
                                         buf.expert_offsets, w["Wg"], w["Wu"], w["Wd"], buf.Yp, buf.workspace, policy)
@@ -284,6 +299,18 @@ def run_layer_workload(args, moe, cpu_baseline: bool):
         route(x, w)
         moe.moe_permute(buf.topk_ids, x, s.E, buf.expert_offsets, buf.src_of_row, buf.row_of_pair, buf.Xp,
                         buf.workspace_permute, materialize=not fused)
+        if fshared:
+            if events is None:
+                run_blocks(x, w, args.policy)
+            else:
+                ev = [[torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)] for _ in names]
+                for i, phase in enumerate((GU, DN)):
+                    ev[i][0].record()
+                    run_blocks(x, w, args.policy | phase)
+                    ev[i][1].record()
+                events.append(ev)
+            moe.moe_combine_parts(buf.Yp, buf.row_of_pair, buf.topk_w, buf.S_parts, buf.sg, buf.out)
+            return
         if events is None:
             run_blocks(x, w, args.policy)
             if sh is not None and not overlap:
@@ -436,8 +463,16 @@ def run_layer_workload(args, moe, cpu_baseline: bool):
                  "routed_down": active * s.I * s.H * 2 + P * s.I * 2 + P * s.H * 2,
                  "shared_gateup": 2 * s.Is * s.H * 2 + s.T * s.H * 2 + s.T * s.Is * 2,
                  "shared_down": s.Is * s.H * 2 + s.T * s.Is * 2 + s.T * s.H * 2}
+    if fshared:
+        # routed and shared experts in the same launches; the shared experts' outputs are written as
+        # Is / I tensors [T,H] (one per shared expert) instead of one
+        n_sets = int(buf.S_parts.shape[0])
+        alg_flops = {"fused_gateup": alg_flops["routed_gateup"] + alg_flops["shared_gateup"],
+                     "fused_down": alg_flops["routed_down"] + alg_flops["shared_down"]}
+        alg_bytes = {"fused_gateup": alg_bytes["routed_gateup"] + alg_bytes["shared_gateup"],
+                     "fused_down": alg_bytes["routed_down"] + alg_bytes["shared_down"] + (n_sets - 1) * s.T * s.H * 2}
     dom = max(kern_ms, key=kern_ms.get)
-    launches = len(groups) if dom.startswith("routed") else 1
+    launches = 1 if dom.startswith("shared") else len(groups)
     dur_s = kern_ms[dom] * 1e-3 / launches      # average duration of one launch
     # Which roof: the grouped GEMMs of prefill-sized batches are matrix-core work (the target is a
     # fraction of the bf16 MFMA peak); at decode sizes the same kernels stream weights (HBM).
@@ -476,7 +511,8 @@ def run_layer_workload(args, moe, cpu_baseline: bool):
                                     f"{max(1, args.tenant_streams)} stream(s); per-kernel figures are the shared orchestrator's"
                                     if private else "shared"),
                    "token_gather": "inside the gate/up kernel (no permuted copy)" if fused else "permuted copy Xp",
-                   "shared_expert_stream": "second stream, concurrent with the routed path" if overlap else "same stream",
+                   "shared_expert": ("inside the first block call, as Is / I experts on every token" if fshared else
+                                     "second stream, concurrent with the routed path" if overlap else "same stream"),
                    "active_experts": active, "rows_per_expert_max": int(counts.max()),
                    "rows_per_expert_median": float(np.median(counts))},
         "ms_per_step_eager": eager_ms, "ms_per_step_graph": graph_ms,

@@ -229,6 +229,48 @@ int moe_expert_group_forward_gather(int group_lo, int group_hi, const void* x,
                                     void* stream);
 
 /*
+ * A block invocation that also hosts the model's shared experts (Sec. 5 "Model Selection": 4 shared
+ * experts per layer beside the 60 routed ones; Sec. 3: a block packages a configurable set of
+ * experts behind one function).  The shared FFN of intermediate size Is is taken as Is / I experts
+ * of the routed experts' size I (gate/up rows [s*I, (s+1)*I) of Wsg, Wsu and columns [s*I, (s+1)*I)
+ * of Wsd are shared expert s), each applied to every token.  Their tiles join the routed experts'
+ * tiles in the same two kernel launches, so the launch has no idle tail between the routed and the
+ * shared part and compute-bound shared tiles run beside memory-bound tiles of small experts.
+ *   Yp rows of the experts in [group_lo, group_hi): as moe_expert_group_forward_gather, bit for bit;
+ *   S_parts[s,t,:] = FFN of shared expert s on x[t,:]  (bf16 [n_sets,T,H]; their sum over s is the
+ *                    shared FFN's output, which moe_combine_parts forms in fp32);
+ *   sg[t] = <x[t,:], wgate> (fp32) when wgate is not NULL.
+ * Supported when moe_fused_shared_sets(T,H,E,K,I,Is) returns n_sets > 0: Is a multiple of I with
+ * at most MOE_SHARED_SETS_MAX sets, E + n_sets <= 256, and a batch large enough for the MFMA tile
+ * kernels (more than 26 rows per routed expert on average); otherwise MOE_ERR_SHAPE, and the
+ * caller uses moe_expert_group_forward(_gather) and moe_shared_forward.  When the routed experts
+ * are cut into several blocks, one of the calls carries the shared experts and the others are
+ * plain block calls.  x [T,H]; src_of_row [T*K]; weights as in the separate calls.
+ * workspace: moe_fused_workspace_bytes(T, K, I, Is) bytes.  policy: 0, 3, 4, 5, 10 or 11 and the
+ * 0x100 / 0x200 bits as for moe_expert_group_forward_ex.
+ */
+#define MOE_SHARED_SETS_MAX 8
+int moe_fused_shared_sets(int T, int H, int E, int K, int I, int Is);
+size_t moe_fused_workspace_bytes(int T, int K, int I, int Is);
+int moe_expert_group_forward_fused(int group_lo, int group_hi, const void* x, const int32_t* src_of_row,
+                                   int K, const int32_t* expert_offsets, const void* Wg,
+                                   const void* Wu, const void* Wd, const void* Wsg, const void* Wsu,
+                                   const void* Wsd, const void* wgate, int T, int H, int E, int I,
+                                   int Is, void* Yp, void* S_parts, float* sg, void* workspace,
+                                   size_t workspace_bytes, int policy, void* stream);
+
+/*
+ * moe_combine for shared-expert outputs that come as n_parts separate tensors (S_parts
+ * [n_parts,T,H] bf16, from moe_expert_group_forward_fused):
+ *   out[t,:] = sum_j topk_w[t,j] * Yp[row_of_pair[t*K+j],:]
+ *              + sigmoid(sg[t]) * (S_parts[0,t,:] + S_parts[1,t,:] + ...)     (fp32, parts in ascending
+ *   order, one rounding to bf16).  1 <= n_parts <= MOE_SHARED_SETS_MAX; S_parts and sg are required.
+ */
+int moe_combine_parts(const void* Yp, const int32_t* row_of_pair, const float* topk_w,
+                      const void* S_parts, int n_parts, const float* sg, int T, int H, int K,
+                      void* out, void* stream);
+
+/*
  * An expert block given as a list of expert ids instead of an id range (Sec. 5 names adaptive,
  * hot-expert-aware block formation as the next step: blocks formed by load need not be ranges).
  * expert_ids [n_ids] int32 ON THE DEVICE, distinct values in [0,E) (not checked); the call

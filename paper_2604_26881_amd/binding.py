@@ -18,7 +18,8 @@ _LIB = None
 
 SYMBOLS = ["moe_status_string", "moe_build_id", "moe_route", "moe_route_segments", "moe_permute", "moe_permute_static", "moe_expert_group_forward",
            "moe_expert_group_forward_ex", "moe_expert_group_forward_gather", "moe_expert_list_forward",
-           "moe_shared_forward", "moe_shared_forward_ex", "moe_combine",
+           "moe_shared_forward", "moe_shared_forward_ex", "moe_combine", "moe_combine_parts",
+           "moe_fused_shared_sets", "moe_fused_workspace_bytes", "moe_expert_group_forward_fused",
            "moe_permute_workspace_bytes", "moe_expert_workspace_bytes", "moe_shared_workspace_bytes",
            "moe_workspace_bytes", "moe_residual_norm"]
 
@@ -79,6 +80,16 @@ def load() -> ctypes.CDLL:
                                           c_int, c_vp]
     lib.moe_combine.restype = c_int
     lib.moe_combine.argtypes = [c_vp, c_vp, c_vp, c_vp, c_vp, c_int, c_int, c_int, c_vp, c_vp]
+    lib.moe_combine_parts.restype = c_int
+    lib.moe_combine_parts.argtypes = [c_vp, c_vp, c_vp, c_vp, c_int, c_vp, c_int, c_int, c_int, c_vp, c_vp]
+    lib.moe_fused_shared_sets.restype = c_int
+    lib.moe_fused_shared_sets.argtypes = [c_int] * 6
+    lib.moe_fused_workspace_bytes.restype = c_sz
+    lib.moe_fused_workspace_bytes.argtypes = [c_int] * 4
+    lib.moe_expert_group_forward_fused.restype = c_int
+    lib.moe_expert_group_forward_fused.argtypes = [c_int, c_int, c_vp, c_vp, c_int, c_vp, c_vp, c_vp, c_vp, c_vp, c_vp,
+                                                   c_vp, c_vp, c_int, c_int, c_int, c_int, c_int, c_vp, c_vp, c_vp, c_vp,
+                                                   c_sz, c_int, c_vp]
     for n in ("moe_permute_workspace_bytes", "moe_expert_workspace_bytes", "moe_shared_workspace_bytes"):
         getattr(lib, n).restype = c_sz
     lib.moe_permute_workspace_bytes.argtypes = [c_int, c_int, c_int]
@@ -313,6 +324,46 @@ def moe_combine(Yp, row_of_pair, topk_w, S, sg, out=None):
     return out
 
 
+def moe_fused_shared_sets(T: int, H: int, E: int, K: int, I: int, Is: int) -> int:
+    """Number of shared-expert sets the fused block call would run for these sizes, 0 when it does not apply."""
+    return int(load().moe_fused_shared_sets(T, H, E, K, I, Is))
+
+
+def moe_expert_group_forward_fused(group_lo: int, group_hi: int, x, src_of_row, K: int, expert_offsets, Wg, Wu, Wd,
+                                   Wsg, Wsu, Wsd, wgate, Yp, S_parts, sg, workspace, policy: int = 0):
+    """The block invocation for experts [group_lo, group_hi) that also runs the shared experts (as Is / I
+    experts of size I on every token) in the same two launches; S_parts [Is / I, T, H]."""
+    T, H = x.shape
+    E, I, _ = Wg.shape
+    Is = Wsg.shape[0]
+    rc = load().moe_expert_group_forward_fused(int(group_lo), int(group_hi), _ptr(x, torch.bfloat16, "x"),
+                                               _ptr(src_of_row, torch.int32, "src_of_row"), int(K),
+                                               _ptr(expert_offsets, torch.int32, "expert_offsets"),
+                                               _ptr(Wg, torch.bfloat16, "Wg"), _ptr(Wu, torch.bfloat16, "Wu"),
+                                               _ptr(Wd, torch.bfloat16, "Wd"), _ptr(Wsg, torch.bfloat16, "Wsg"),
+                                               _ptr(Wsu, torch.bfloat16, "Wsu"), _ptr(Wsd, torch.bfloat16, "Wsd"),
+                                               _ptr(wgate, torch.bfloat16, "wgate"), T, H, E, I, Is,
+                                               _ptr(Yp, torch.bfloat16, "Yp"), _ptr(S_parts, torch.bfloat16, "S_parts"),
+                                               _ptr(sg, torch.float32, "sg"), _ptr(workspace, None, "workspace"),
+                                               0 if workspace is None else workspace.numel() * workspace.element_size(),
+                                               int(policy), _stream())
+    _check(rc, "moe_expert_group_forward_fused")
+    return Yp, S_parts, sg
+
+
+def moe_combine_parts(Yp, row_of_pair, topk_w, S_parts, sg, out=None):
+    T, K = topk_w.shape
+    H = Yp.shape[1]
+    if out is None:
+        out = torch.empty((T, H), dtype=torch.bfloat16, device=Yp.device)
+    rc = load().moe_combine_parts(_ptr(Yp, torch.bfloat16, "Yp"), _ptr(row_of_pair, torch.int32, "row_of_pair"),
+                                  _ptr(topk_w, torch.float32, "topk_w"), _ptr(S_parts, torch.bfloat16, "S_parts"),
+                                  int(S_parts.shape[0]), _ptr(sg, torch.float32, "sg"), T, H, K,
+                                  _ptr(out, torch.bfloat16, "out"), _stream())
+    _check(rc, "moe_combine_parts")
+    return out
+
+
 def moe_residual_norm(x, y, out=None, eps: float = 1e-6):
     T, H = x.shape
     if out is None:
@@ -339,6 +390,8 @@ class LayerBuffers:
     workspace: torch.Tensor
     workspace_shared: Optional[torch.Tensor]
     workspace_permute: Optional[torch.Tensor] = None
+    S_parts: Optional[torch.Tensor] = None          # [Is / I, T, H]: outputs of the shared experts of the fused block call
+    workspace_fused: Optional[torch.Tensor] = None
 
     @staticmethod
     def allocate(T: int, H: int, E: int, K: int, I: int, Is: int, device="cuda") -> "LayerBuffers":
@@ -348,7 +401,13 @@ class LayerBuffers:
         bf = dict(dtype=torch.bfloat16, device=device)
         ws = max(int(lib.moe_expert_workspace_bytes(P, I)), 256)
         wss = int(lib.moe_shared_workspace_bytes(T, H, Is))
-        return LayerBuffers(
+        ns = int(lib.moe_fused_shared_sets(T, H, E, K, I, Is)) if Is > 0 else 0
+        fused = {}
+        if ns > 0:     # the fused call's h holds the routed rows and then the rows of every shared set
+            fused = dict(S_parts=torch.empty((ns, T, H), **bf),
+                         workspace_fused=torch.empty(int(lib.moe_fused_workspace_bytes(T, K, I, Is)), dtype=torch.uint8,
+                                                     device=device))
+        return LayerBuffers(**fused,
             topk_ids=torch.empty((T, K), **i32), topk_w=torch.empty((T, K), dtype=torch.float32, device=device),
             expert_offsets=torch.empty(E + 1, **i32), src_of_row=torch.empty(P, **i32),
             row_of_pair=torch.empty(P, **i32), Xp=torch.empty((P, H), **bf), Yp=torch.empty((P, H), **bf),
@@ -364,7 +423,8 @@ def moe_layer_forward(x, Wr, bias, Wg, Wu, Wd, shared, K: int, renorm: bool,
                       groups: Optional[Sequence[Tuple[int, int]]] = None, buf: Optional[LayerBuffers] = None,
                       tenant_rows: Optional[List[Tuple[int, int]]] = None, policy: int = 0,
                       shared_policy: int = 0, shared_stream: Optional[torch.cuda.Stream] = None,
-                      fused_gather: bool = False, seg_offsets: Optional[torch.Tensor] = None) -> LayerBuffers:
+                      fused_gather: bool = False, seg_offsets: Optional[torch.Tensor] = None,
+                      fused_shared: bool = False) -> LayerBuffers:
     """One MoE layer in the paper's order: gating, micro-batch construction, one call per expert
     block, shared expert, aggregation.  Sequencing only; every step is a library call.
 
@@ -374,7 +434,10 @@ def moe_layer_forward(x, Wr, bias, Wg, Wu, Wd, shared, K: int, renorm: bool,
     it when the call is captured into a graph); slices that are not consecutive are gated one by one.
     shared_stream: run the shared expert on this stream, concurrently with gating, permutation and
     the routed blocks (it depends on x only); the aggregation waits for it.
-    fused_gather: no permuted copy Xp; the block calls read x through src_of_row."""
+    fused_gather: no permuted copy Xp; the block calls read x through src_of_row.
+    fused_shared: the first block call also runs the shared experts (moe_expert_group_forward_fused, which
+    reads x through src_of_row) and the aggregation takes their outputs as separate parts; sizes the fused
+    call does not serve fall back to the separate calls."""
     T, H = x.shape
     E, I, _ = Wg.shape
     Is = 0 if shared is None else shared[0].shape[0]
@@ -382,6 +445,9 @@ def moe_layer_forward(x, Wr, bias, Wg, Wu, Wd, shared, K: int, renorm: bool,
         buf = LayerBuffers.allocate(T, H, E, K, I, Is, x.device)
     main = torch.cuda.current_stream()
     fork = None
+    fused_shared = bool(fused_shared and shared is not None and buf.S_parts is not None)
+    if fused_shared:
+        fused_gather, shared_stream = True, None
     if shared is not None and shared_stream is not None:
         fork = torch.cuda.Event()     # the shared expert needs x only: its branch forks off here
         fork.record(main)
@@ -397,12 +463,19 @@ def moe_layer_forward(x, Wr, bias, Wg, Wu, Wd, shared, K: int, renorm: bool,
         moe_route(x, Wr, bias, K, renorm, buf.topk_ids, buf.topk_w)
     moe_permute(buf.topk_ids, x, E, buf.expert_offsets, buf.src_of_row, buf.row_of_pair, buf.Xp,
                 buf.workspace_permute, materialize=not fused_gather)
-    for lo, hi in (groups or [(0, E)]):
-        if fused_gather:
+    for i, (lo, hi) in enumerate(groups or [(0, E)]):
+        if fused_shared and i == 0:
+            moe_expert_group_forward_fused(lo, hi, x, buf.src_of_row, K, buf.expert_offsets, Wg, Wu, Wd, shared[0],
+                                           shared[1], shared[2], shared[3], buf.Yp, buf.S_parts, buf.sg,
+                                           buf.workspace_fused, policy)
+        elif fused_gather:
             moe_expert_group_forward_gather(lo, hi, x, buf.src_of_row, K, buf.expert_offsets, Wg, Wu, Wd, buf.Yp,
                                             buf.workspace, policy)
         else:
             moe_expert_group_forward(lo, hi, buf.Xp, buf.expert_offsets, Wg, Wu, Wd, buf.Yp, buf.workspace, policy)
+    if fused_shared:
+        moe_combine_parts(buf.Yp, buf.row_of_pair, buf.topk_w, buf.S_parts, buf.sg, buf.out)
+        return buf
     if shared is not None and shared_stream is None:
         moe_shared_forward(x, shared[0], shared[1], shared[2], shared[3], buf.S, buf.sg, buf.workspace_shared,
                            shared_policy)

@@ -232,6 +232,59 @@ int moe_expert_list_forward(const int32_t* expert_ids, int n_ids, const void* to
                                    Wd, P, H, E, I, Yp, workspace, workspace_bytes, policy, stream);
 }
 
+int moe_fused_shared_sets(int T, int H, int E, int K, int I, int Is) {
+  if (T <= 0 || K < 1 || E < 1 || I <= 0 || Is <= 0 || !dims_ok(H) || !dims_ok(I) || Is % I != 0) return 0;
+  const int ns = Is / I;
+  if (ns > MOE_SHARED_SETS_MAX || E + ns > 256) return 0;
+  const long long P = (long long)T * K;
+  if ((P + (long long)ns * T) * (H > I ? H : I) >= (1ll << 31)) return 0;
+  const Plan plan = make_plan((int)((P + E - 1) / E), E, 0);
+  return plan.stream ? 0 : ns;     // batches served by weight streaming keep the separate calls
+}
+
+size_t moe_fused_workspace_bytes(int T, int K, int I, int Is) {
+  if (T <= 0 || K <= 0 || I <= 0 || Is <= 0 || Is % I != 0) return 0;
+  return align256(((size_t)T * K + (size_t)(Is / I) * T) * (size_t)I * 2);
+}
+
+int moe_expert_group_forward_fused(int group_lo, int group_hi, const void* x, const int32_t* src_of_row, int K,
+                                   const int32_t* expert_offsets, const void* Wg, const void* Wu, const void* Wd,
+                                   const void* Wsg, const void* Wsu, const void* Wsd, const void* wgate, int T, int H,
+                                   int E, int I, int Is, void* Yp, void* S_parts, float* sg, void* workspace,
+                                   size_t workspace_bytes, int policy, void* stream) {
+  if (T < 0 || K < 1 || K > 16 || !dims_ok(H) || !dims_ok(I) || E < 1 || E > 256) return MOE_ERR_SHAPE;
+  if (group_lo < 0 || group_hi > E || group_lo >= group_hi) return MOE_ERR_SHAPE;
+  if (T == 0) return MOE_OK;
+  const int ns = moe_fused_shared_sets(T, H, E, K, I, Is);
+  if (ns == 0) return MOE_ERR_SHAPE;
+  if (!x || !src_of_row || !expert_offsets || !Wg || !Wu || !Wd || !Wsg || !Wsu || !Wsd || !Yp || !S_parts || !workspace)
+    return MOE_ERR_NULL;
+  if (wgate && !sg) return MOE_ERR_NULL;
+  const int P = T * K;
+  const int rows = P + ns * T;
+  if (workspace_bytes < (size_t)rows * (size_t)I * 2) return MOE_ERR_WORKSPACE;   // h of the routed rows, then of every shared set
+  const int mean_rows = (P + E - 1) / E;
+  const Plan plan = make_plan(mean_rows, E, policy);
+  if (!plan.valid || plan.stream || plan.tile_rows == 64) return MOE_ERR_SHAPE;
+  GemmArgs gu{};
+  gu.A = (const bf16_t*)x; gu.B0 = (const bf16_t*)Wg; gu.B1 = (const bf16_t*)Wu; gu.C = (bf16_t*)workspace;
+  gu.offsets = expert_offsets; gu.lo = group_lo; gu.hi = group_hi; gu.ids = nullptr; gu.rows_total = rows;
+  gu.mean_rows = mean_rows; gu.N = I; gu.Kdim = H;
+  gu.n_shared = ns; gu.shared_rows = T; gu.rows_routed = P;
+  GemmArgs dn = gu;
+  gu.gather = src_of_row; gu.gather_div = K;
+  gu.Bs0 = (const bf16_t*)Wsg; gu.Bs1 = (const bf16_t*)Wsu; gu.shared_b_step = (long)I * H; gu.ldb_shared = H;
+  gu.As = (const bf16_t*)x;                 // set s of the shared expert reads the tokens in order
+  dn.A = (const bf16_t*)workspace; dn.B0 = (const bf16_t*)Wd; dn.B1 = nullptr; dn.C = (bf16_t*)Yp;
+  dn.N = H; dn.Kdim = I;
+  dn.Bs0 = (const bf16_t*)Wsd; dn.shared_b_step = I; dn.ldb_shared = Is;   // set s: columns [s*I, (s+1)*I) of Wsd [H,Is]
+  dn.Cs = (bf16_t*)S_parts;
+  int rc = ffn_forward(gu, dn, plan, (hipStream_t)stream);
+  if (rc != 0) return rc;
+  if (wgate && plan.do_down) return launch_gate_dot(x, wgate, T, H, sg, (hipStream_t)stream);
+  return MOE_OK;
+}
+
 int moe_expert_group_forward(int group_lo, int group_hi, const void* Xp, const int32_t* expert_offsets,
                              const void* Wg, const void* Wu, const void* Wd, int P, int H, int E, int I, void* Yp,
                              void* workspace, size_t workspace_bytes, void* stream) {
@@ -287,7 +340,15 @@ int moe_combine(const void* Yp, const int32_t* row_of_pair, const float* topk_w,
   if (T == 0) return MOE_OK;
   if (!Yp || !row_of_pair || !topk_w || !out) return MOE_ERR_NULL;
   if ((S == nullptr) != (sg == nullptr)) return MOE_ERR_NULL;
-  return launch_combine(Yp, row_of_pair, topk_w, S, sg, T, H, K, out, (hipStream_t)stream);
+  return launch_combine(Yp, row_of_pair, topk_w, S, 1, sg, T, H, K, out, (hipStream_t)stream);
+}
+
+int moe_combine_parts(const void* Yp, const int32_t* row_of_pair, const float* topk_w, const void* S_parts, int n_parts,
+                      const float* sg, int T, int H, int K, void* out, void* stream) {
+  if (T < 0 || !dims_ok(H) || K < 1 || K > 16 || n_parts < 1 || n_parts > MOE_SHARED_SETS_MAX) return MOE_ERR_SHAPE;
+  if (T == 0) return MOE_OK;
+  if (!Yp || !row_of_pair || !topk_w || !out || !S_parts || !sg) return MOE_ERR_NULL;
+  return launch_combine(Yp, row_of_pair, topk_w, S_parts, n_parts, sg, T, H, K, out, (hipStream_t)stream);
 }
 
 int moe_residual_norm(const void* x, const void* y, int T, int H, float eps, void* out, void* stream) {

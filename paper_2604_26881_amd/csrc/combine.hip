@@ -1,5 +1,7 @@
 // Aggregation (FaaSMoE Sec. 3 and Sec. 4.2: the orchestrator aggregates what the expert blocks
-// return).  out[t,:] = sum_j topk_w[t,j] * Yp[row_of_pair[t*K+j],:] + sigmoid(sg[t]) * S[t,:].
+// return).  out[t,:] = sum_j topk_w[t,j] * Yp[row_of_pair[t*K+j],:] + sigmoid(sg[t]) * S[t,:],
+// where S may come as the separate outputs of the shared experts (n_parts tensors [T,H], added in
+// fp32 in ascending order before the gate is applied).
 //
 // A gather, not a scatter: one workgroup per token reads its K expert rows (and the shared
 // row) with 16-byte loads, accumulates in fp32 in slot order j = 0..K-1 and rounds once to
@@ -13,8 +15,9 @@ constexpr int COMBINE_KMAX = 16;
 __global__ __launch_bounds__(256) void combine_kernel(const bf16_t* __restrict__ Yp,
                                                       const int32_t* __restrict__ row_of_pair,
                                                       const float* __restrict__ topk_w,
-                                                      const bf16_t* __restrict__ S, const float* __restrict__ sg,
-                                                      int H, int K, bf16_t* __restrict__ out) {
+                                                      const bf16_t* __restrict__ S, int n_parts, long part_stride,
+                                                      const float* __restrict__ sg, int H, int K,
+                                                      bf16_t* __restrict__ out) {
   const int t = blockIdx.x;
   __shared__ int s_row[COMBINE_KMAX];
   __shared__ float s_w[COMBINE_KMAX];
@@ -34,6 +37,16 @@ __global__ __launch_bounds__(256) void combine_kernel(const bf16_t* __restrict__
     // (the sum still takes the rows in slot order)
     uint4 vs = {0u, 0u, 0u, 0u};
     if (S != nullptr) vs = reinterpret_cast<const uint4*>(S + (size_t)t * H)[c];
+    float sh[8];
+    if (n_parts > 1) {   // the shared experts' outputs come as separate tensors: summed first, in order
+      sh[0] = bf16_lo(vs.x); sh[1] = bf16_hi(vs.x); sh[2] = bf16_lo(vs.y); sh[3] = bf16_hi(vs.y);
+      sh[4] = bf16_lo(vs.z); sh[5] = bf16_hi(vs.z); sh[6] = bf16_lo(vs.w); sh[7] = bf16_hi(vs.w);
+      for (int p = 1; p < n_parts; ++p) {
+        const uint4 v = reinterpret_cast<const uint4*>(S + (size_t)p * part_stride + (size_t)t * H)[c];
+        sh[0] += bf16_lo(v.x); sh[1] += bf16_hi(v.x); sh[2] += bf16_lo(v.y); sh[3] += bf16_hi(v.y);
+        sh[4] += bf16_lo(v.z); sh[5] += bf16_hi(v.z); sh[6] += bf16_lo(v.w); sh[7] += bf16_hi(v.w);
+      }
+    }
     for (int j0 = 0; j0 < K; j0 += 4) {
       uint4 vv[4];
 #pragma unroll
@@ -51,7 +64,10 @@ __global__ __launch_bounds__(256) void combine_kernel(const bf16_t* __restrict__
         }
       }
     }
-    if (S != nullptr) {
+    if (S != nullptr && n_parts > 1) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) acc[i] = __builtin_fmaf(gate, sh[i], acc[i]);
+    } else if (S != nullptr) {
       const uint4 v = vs;
       acc[0] = __builtin_fmaf(gate, bf16_lo(v.x), acc[0]); acc[1] = __builtin_fmaf(gate, bf16_hi(v.x), acc[1]);
       acc[2] = __builtin_fmaf(gate, bf16_lo(v.y), acc[2]); acc[3] = __builtin_fmaf(gate, bf16_hi(v.y), acc[3]);
@@ -137,11 +153,11 @@ int launch_residual_norm(const void* x, const void* y, int T, int H, float eps, 
   return hipGetLastError() == hipSuccess ? 0 : -4;
 }
 
-int launch_combine(const void* Yp, const int32_t* row_of_pair, const float* w, const void* S, const float* sg,
-                   int T, int H, int K, void* out, hipStream_t st) {
+int launch_combine(const void* Yp, const int32_t* row_of_pair, const float* w, const void* S, int n_parts,
+                   const float* sg, int T, int H, int K, void* out, hipStream_t st) {
   if (T == 0) return 0;
   hipLaunchKernelGGL(combine_kernel, dim3(T), dim3(256), 0, st, (const bf16_t*)Yp, row_of_pair, w,
-                     (const bf16_t*)S, sg, H, K, (bf16_t*)out);
+                     (const bf16_t*)S, n_parts, (long)T * H, sg, H, K, (bf16_t*)out);
   return hipGetLastError() == hipSuccess ? 0 : -4;
 }
 

@@ -93,6 +93,18 @@ struct GemmArgs {
   int gather_div;          // (the token rows themselves, addressed through src_of_row: no permuted copy)
   int leave_room;          // 1: no tile shape that takes a whole CU (all registers of every SIMD): kernels of
                            // other streams can then share the CUs with this one
+  // Shared experts riding along with a routed block (tile kernels only; n_shared == 0: none).  They are
+  // n_shared more weight sets, each applied to all shared_rows tokens.  In the row space of A and C
+  // the routed rows are [0, rows_routed) and set s owns rows rows_routed + s*shared_rows onwards.
+  int n_shared;
+  int shared_rows;         // tokens T
+  int rows_routed;         // P
+  const bf16_t* Bs0;       // weights of set 0 (gate branch, or the down projection); set s starts s*shared_b_step
+  const bf16_t* Bs1;       // elements further on; consecutive weight rows of a set are ldb_shared elements apart
+  long shared_b_step;
+  int ldb_shared;
+  const bf16_t* As;        // not nullptr: set s reads its token rows from As[0 .. shared_rows) instead of A (gate/up: x)
+  bf16_t* Cs;              // not nullptr: row r of set s goes to Cs[s*shared_rows + r] instead of C (down: the S parts)
 };
 
 // bias [E] for all tokens (seg == nullptr), or bias [n_seg, E] with seg [n_seg + 1] segment bounds on the device
@@ -100,8 +112,8 @@ int launch_route(const void* x, const void* Wr, const float* bias, const int32_t
                  int K, int renorm, int32_t* ids, float* w, hipStream_t st);
 int launch_permute(const int32_t* ids, const void* x, int T, int H, int E, int K, int32_t* offsets,
                    int32_t* src_of_row, int32_t* row_of_pair, void* Xp, void* workspace, hipStream_t st);
-int launch_combine(const void* Yp, const int32_t* row_of_pair, const float* w, const void* S, const float* sg,
-                   int T, int H, int K, void* out, hipStream_t st);
+int launch_combine(const void* Yp, const int32_t* row_of_pair, const float* w, const void* S, int n_parts,
+                   const float* sg, int T, int H, int K, void* out, hipStream_t st);
 int launch_residual_norm(const void* x, const void* y, int T, int H, float eps, void* out, hipStream_t st);
 int launch_gate_dot(const void* x, const void* wgate, int T, int H, float* sg, hipStream_t st);
 // Tiled MFMA kernels (many rows per expert) and streaming kernels (few rows per expert).

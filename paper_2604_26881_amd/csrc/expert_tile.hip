@@ -98,7 +98,9 @@ __global__ __launch_bounds__(256, OCC) void expert_tile_kernel(GemmArgs a) {
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave / WAVES_N, wn = wave % WAVES_N;
-  const int nexp = a.offsets ? a.hi - a.lo : 1;
+  // weight sets of this launch: the routed experts of the block, then the shared sets riding along
+  const int nrouted = a.offsets ? a.hi - a.lo : (a.n_shared > 0 ? 0 : 1);
+  const int nexp = nrouted + a.n_shared;     // at most TILE_EMAX (checked by the caller)
 
   // per-expert row range and number of token tiles -> exclusive prefix per class in LDS
   if (wave == 0) {
@@ -108,9 +110,10 @@ __global__ __launch_bounds__(256, OCC) void expert_tile_kernel(GemmArgs a) {
       const int e = lane * 4 + i;
       v[i] = 0;
       if (e < nexp) {
-        const int eid = a.offsets ? (a.ids ? a.ids[a.lo + e] : a.lo + e) : 0;
-        const int rb = a.offsets ? a.offsets[eid] : 0;
-        const int re = a.offsets ? a.offsets[eid + 1] : a.rows_fixed;
+        const bool sh = e >= nrouted;
+        const int eid = sh ? e - nrouted : (a.offsets ? (a.ids ? a.ids[a.lo + e] : a.lo + e) : 0);
+        const int rb = sh ? a.rows_routed + eid * a.shared_rows : (a.offsets ? a.offsets[eid] : 0);
+        const int re = sh ? rb + a.shared_rows : (a.offsets ? a.offsets[eid + 1] : a.rows_fixed);
         s_eid[e] = (uint8_t)eid;
         s_rb[e] = rb;
         v[i] = (max(re - rb, 0) + BM - 1) / BM;
@@ -175,7 +178,7 @@ __global__ __launch_bounds__(256, OCC) void expert_tile_kernel(GemmArgs a) {
   // State of a tile: the current one (being multiplied, then stored) and, while the current one is
   // stored, the next one, whose first NS stages are already requested: the latency of those copies
   // hides behind the epilogue instead of opening every tile.
-  struct TileState { int row0, rowEnd, rowsValid, n0, ks; bool valid; };
+  struct TileState { int row0, rowEnd, rowsValid, n0, ks, cshift; bf16_t* cbase; bool valid; };
   const unsigned char *Ag = nullptr, *Bg0 = nullptr, *Bg1 = nullptr;
   uint32_t coff[S::NL];   // byte offsets of this lane's 16 bytes for each of the NL copies of a stage (K step 0)
   int it = 0;
@@ -207,30 +210,44 @@ __global__ __launch_bounds__(256, OCC) void expert_tile_kernel(GemmArgs a) {
     }
     // (the same in every lane: readfirstlane keeps them in scalar registers)
     const int e = __builtin_amdgcn_readfirstlane(elo);
-    const int eg = __builtin_amdgcn_readfirstlane((int)s_eid[e]);
-    t.row0 = __builtin_amdgcn_readfirstlane(s_rb[e] + (mrow - s_pref[cls][e]) * BM);
-    t.rowEnd = a.offsets ? a.offsets[eg + 1] : a.rows_fixed;
+    const int eg = __builtin_amdgcn_readfirstlane((int)s_eid[e]);   // expert id, or the number of the shared set
+    const bool sh = e >= nrouted;
+    const int rb = __builtin_amdgcn_readfirstlane(s_rb[e]);
+    t.row0 = __builtin_amdgcn_readfirstlane(rb + (mrow - s_pref[cls][e]) * BM);
+    t.rowEnd = sh ? rb + a.shared_rows : (a.offsets ? a.offsets[eg + 1] : a.rows_fixed);
     t.rowsValid = min(BM, t.rowEnd - t.row0);
     t.n0 = nt * S::NOUT;
+    // where this tile's rows go: a shared set may have an output tensor of its own
+    const bool own_c = sh && a.Cs != nullptr;
+    t.cbase = own_c ? a.Cs : a.C;
+    t.cshift = own_c ? a.rows_routed : 0;
 
     const size_t kbeg = (size_t)t.ks * nk * S::BK;
-    // with a gather list the token rows are addressed from the start of A, through the list
-    Ag = reinterpret_cast<const unsigned char*>(a.A + (a.gather ? (size_t)0 : (size_t)t.row0 * Kdim) + kbeg);
-    Bg0 = reinterpret_cast<const unsigned char*>(a.B0 + (size_t)eg * a.N * Kdim + kbeg);
-    Bg1 = GATEUP ? reinterpret_cast<const unsigned char*>(a.B1 + (size_t)eg * a.N * Kdim + kbeg) : nullptr;
+    // token rows: with a gather list they are addressed from the start of A, through the list; a
+    // shared set with token rows of its own reads them in order
+    const bool own_a = sh && a.As != nullptr;
+    const bool gathered = a.gather != nullptr && !own_a;
+    Ag = reinterpret_cast<const unsigned char*>(
+        own_a ? a.As + (size_t)(t.row0 - rb) * Kdim + kbeg : a.A + (gathered ? (size_t)0 : (size_t)t.row0 * Kdim) + kbeg);
+    const uint32_t ldb = sh ? (uint32_t)a.ldb_shared : (uint32_t)Kdim;   // elements between consecutive weight rows
+    Bg0 = reinterpret_cast<const unsigned char*>((sh ? a.Bs0 + (size_t)eg * a.shared_b_step : a.B0 + (size_t)eg * a.N * Kdim) + kbeg);
+    Bg1 = GATEUP ? reinterpret_cast<const unsigned char*>((sh ? a.Bs1 + (size_t)eg * a.shared_b_step : a.B1 + (size_t)eg * a.N * Kdim) + kbeg)
+                 : nullptr;
 #pragma unroll
     for (int i = 0; i < S::NL; ++i) {
       const int row = (i * 4 + wave) * 8 + crow;        // row inside the stage: tokens first, then weights
       int grow;
+      uint32_t ld = (uint32_t)Kdim;
       if (i < S::NLA) {
         grow = min(row, t.rowsValid - 1);
-        if (a.gather) grow = a.gather[t.row0 + grow] / a.gather_div;
+        if (gathered) grow = a.gather[t.row0 + grow] / a.gather_div;
       } else {
         int r = row - BM;
         if (GATEUP && i >= S::NLA + (S::NL - S::NLA) / 2) r -= BN / 2;   // second half: the up branch
         grow = min(t.n0 + r, a.N - 1);
+        ld = ldb;
       }
-      coff[i] = (uint32_t)grow * (uint32_t)Kdim * 2u + (uint32_t)cchunk * 16u;
+      coff[i] = (uint32_t)grow * ld * 2u + (uint32_t)cchunk * 16u;
     }
     // all NS stages of the tile are requested up front
 #pragma unroll
@@ -241,6 +258,8 @@ __global__ __launch_bounds__(256, OCC) void expert_tile_kernel(GemmArgs a) {
   TileState cur = next_tile();
   while (cur.valid) {
     const int row0 = cur.row0, rowEnd = cur.rowEnd, rowsValid = cur.rowsValid, n0 = cur.n0, ks = cur.ks;
+    bf16_t* const cbase = cur.cbase;
+    const int cshift = cur.cshift;
     f32x16 acc[S::NB][S::TB];
 #pragma unroll
     for (int nb = 0; nb < S::NB; ++nb)
@@ -403,7 +422,7 @@ __global__ __launch_bounds__(256, OCC) void expert_tile_kernel(GemmArgs a) {
     for (int tb = 0; tb < S::TB; ++tb) {
       const int m = row0 + wm * S::WTM + tb * 32 + frag_row;
       if (m < rowEnd) {
-        bf16_t* crow_out = a.C + (size_t)m * a.N;
+        bf16_t* crow_out = cbase + (size_t)(m - cshift) * a.N;
 #pragma unroll
         for (int nb = 0; nb < S::NBH; ++nb) {
           const int nblock = n0 + (GATEUP ? wn * (S::WTN / 2) : wn * S::WTN) + nb * 32;   // first column of the 32-column block
@@ -492,7 +511,8 @@ static int launch_tile_t(const GemmArgs& a, hipStream_t st) {
     if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess) return -4;
     if (dev < 64) attr_done.fetch_or(bit, std::memory_order_release);
   }
-  const int nexp = a.offsets ? a.hi - a.lo : 1;
+  const int nexp = (a.offsets ? a.hi - a.lo : (a.n_shared > 0 ? 0 : 1)) + a.n_shared;
+  if (nexp > TILE_EMAX) return -2;
   const int NT = (a.N + S::NOUT - 1) / S::NOUT;
   const long mt_bound = (long)a.rows_total / BM + nexp;
   const long bound = ((mt_bound + S::GM - 1) / S::GM) * S::GM * NT * KSPLIT;

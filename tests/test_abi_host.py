@@ -114,6 +114,26 @@ def test_bad_arguments_are_rejected_before_any_launch(lib):
     assert lib.moe_route(p, p, None, 4, 8256, 8, 2, 0, p, p, None) == SHAPE
     assert lib.moe_route_segments(p, p, p, p, 2, 4, 8256, 8, 2, 0, p, p, None) == SHAPE
     assert lib.moe_residual_norm(p, p, 4, 8256, ctypes.c_float(1e-6), p, None) == SHAPE
+    # block call that hosts the shared experts
+    fu = lambda T, I, Is, ws, pol=0, x=p, E=8: lib.moe_expert_group_forward_fused(0, 8, x, p, 2, p, p, p, p, p, p, p, p, T, 64,
+                                                                                  E, I, Is, p, p, p, p, ws, pol, None)
+    assert lib.moe_fused_shared_sets(512, 64, 8, 2, 128, 512) == 4
+    assert lib.moe_fused_shared_sets(512, 64, 8, 2, 128, 448) == 0          # Is is not a multiple of I
+    assert lib.moe_fused_shared_sets(512, 64, 8, 2, 128, 128 * 9) == 0      # more than 8 sets
+    assert lib.moe_fused_shared_sets(64, 64, 60, 2, 128, 512) == 0          # a batch for the weight-streaming kernels
+    assert lib.moe_fused_shared_sets(512, 64, 254, 2, 128, 512) == 0        # E + sets > 256
+    assert lib.moe_fused_workspace_bytes(512, 2, 128, 512) == (1024 + 4 * 512) * 128 * 2
+    assert fu(512, 128, 448, 1 << 24) == SHAPE
+    assert fu(64, 128, 512, 1 << 24, E=60) == SHAPE
+    assert fu(512, 128, 512, 1 << 24, 9) == SHAPE                           # streaming kernels cannot host them
+    assert fu(512, 128, 512, 1 << 24, 8) == SHAPE
+    assert fu(512, 128, 512, 1000) == WS
+    assert fu(512, 128, 512, 1 << 24, 0, None) == NULL
+    assert fu(0, 128, 512, 0) == 0
+    assert lib.moe_combine_parts(p, p, p, p, 0, p, 4, 64, 2, p, None) == SHAPE
+    assert lib.moe_combine_parts(p, p, p, p, 9, p, 4, 64, 2, p, None) == SHAPE
+    assert lib.moe_combine_parts(p, p, p, None, 2, p, 4, 64, 2, p, None) == NULL
+    assert lib.moe_combine_parts(p, p, p, p, 2, None, 4, 64, 2, p, None) == NULL
     # combine
     assert lib.moe_combine(p, p, p, p, None, 4, 64, 2, p, None) == NULL      # S without sg
     assert lib.moe_combine(p, p, p, None, None, 4, 64, 17, p, None) == SHAPE

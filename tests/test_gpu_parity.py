@@ -479,6 +479,75 @@ def test_shared_expert_automatic_shapes_match_oracle(moe, oracle64, T, H, Is):
     assert np.allclose(sg.cpu().numpy(), sg_ref, rtol=1e-4, atol=1e-5)
 
 
+def oracle_shared_parts(oracle64, d, I):
+    """The shared FFN as Is / I experts of the routed size (Sec. 5: the model has 4 shared experts): part s
+    uses gate/up rows and down columns [s*I, (s+1)*I); the parts add up to the shared FFN's output."""
+    Is = d["Wsg"].shape[0]
+    parts = []
+    for s0 in range(0, Is, I):
+        S, _ = oracle64.shared_forward(d["x"], d["Wsg"][s0:s0 + I], d["Wsu"][s0:s0 + I],
+                                       np.ascontiguousarray(d["Wsd"][:, s0:s0 + I]), None)
+        parts.append(S)
+    return np.stack(parts)
+
+
+@pytest.mark.parametrize("policy", [0, 3, 4, 5, 10, 11])
+def test_block_call_that_hosts_the_shared_experts_matches_oracle(moe, oracle64, policy):
+    # routed experts and the shared experts (3 sets of the routed size) in the same two launches
+    wl = skewed_workload(T=700, H=256, E=20, K=4, I=192, Is=576, seed=71)
+    s = wl.shape
+    d = wl.f32_numpy()
+    ref = oracle64.layer(d["x"], d["Wr"], d["bias"], d["Wg"], d["Wu"], d["Wd"], shared_of(d), s.K, s.renorm)
+    parts_ref = oracle_shared_parts(oracle64, d, s.I)
+    assert np.allclose(parts_ref.sum(axis=0), ref["S"], rtol=1e-9, atol=1e-12)
+    g = wl.to("cuda")
+    assert moe.moe_fused_shared_sets(s.T, s.H, s.E, s.K, s.I, s.Is) == 3
+    ids, w = moe.moe_route(g.x, g.Wr, g.bias, s.K, s.renorm)
+    off, src, rowp, _ = moe.moe_permute(ids, g.x, s.E, materialize=False)
+    ws = torch.empty(int(moe.load().moe_fused_workspace_bytes(s.T, s.K, s.I, s.Is)), dtype=torch.uint8, device="cuda")
+    Yp = torch.full((s.P, s.H), 768.0, dtype=torch.bfloat16, device="cuda")
+    Sp = torch.full((3, s.T, s.H), 768.0, dtype=torch.bfloat16, device="cuda")
+    sg = torch.empty(s.T, dtype=torch.float32, device="cuda")
+    lo, hi = 6, 20
+    print(f"[case] block call hosting the shared experts, policy {policy}", flush=True)
+    moe.moe_expert_group_forward_fused(lo, hi, g.x, src, s.K, off, g.Wg, g.Wu, g.Wd, g.Wsg, g.Wsu, g.Wsd, g.wgate, Yp, Sp, sg,
+                                       ws, policy)
+    torch.cuda.synchronize()
+    a, b = int(ref["offsets"][lo]), int(ref["offsets"][hi])
+    y = f64(Yp)
+    assert np.all(y[:a] == 768.0) and np.all(y[b:] == 768.0), "rows outside the block were written"
+    check_close(y[a:b], ref["Yp"][a:b], f"Yp rows of the block that hosts the shared experts, policy {policy}")
+    for i in range(3):
+        check_close(f64(Sp[i]), parts_ref[i], f"shared expert {i} of 3, policy {policy}")
+    assert np.allclose(sg.cpu().numpy(), ref["sg"], rtol=1e-4, atol=1e-5)
+    # the routed rows are those of the plain gather call, bit for bit
+    ws2 = torch.empty(s.P * s.I * 2, dtype=torch.uint8, device="cuda")
+    Y2 = torch.full((s.P, s.H), 768.0, dtype=torch.bfloat16, device="cuda")
+    moe.moe_expert_group_forward_gather(lo, hi, g.x, src, s.K, off, g.Wg, g.Wu, g.Wd, Y2, ws2, policy)
+    moe.moe_expert_group_forward_gather(0, lo, g.x, src, s.K, off, g.Wg, g.Wu, g.Wd, Yp, ws2, policy)
+    out = moe.moe_combine_parts(Yp, rowp, w, Sp, sg)
+    torch.cuda.synchronize()
+    assert torch.equal(Yp[a:b].view(torch.int16), Y2[a:b].view(torch.int16))
+    check_close(f64(out), ref["out"], f"layer output, shared experts hosted by a block, policy {policy}")
+
+
+def test_combine_over_shared_parts_matches_oracle(moe, oracle64):
+    T, H, K, n = 37, 192, 3, 5
+    g = torch.Generator().manual_seed(19)
+    Yp = torch.randn((T * K, H), generator=g).to(torch.bfloat16)
+    Sp = torch.randn((n, T, H), generator=g).to(torch.bfloat16)
+    sg = torch.randn((T,), generator=g)
+    w = torch.rand((T, K), generator=g)
+    rowp = torch.randperm(T * K, generator=g).to(torch.int32)
+    S = Sp.double().sum(dim=0).numpy()       # the parts add up to the shared output (exact in float64)
+    ref = oracle64.combine(Yp.float().numpy(), rowp.numpy(), w.numpy(), S, sg.numpy(), K)
+    out = moe.moe_combine_parts(Yp.cuda(), rowp.cuda(), w.cuda(), Sp.cuda(), sg.cuda())
+    check_close(f64(out), ref, "combine over five shared parts", tight=4e-3)
+    one = moe.moe_combine_parts(Yp.cuda(), rowp.cuda(), w.cuda(), Sp[:1].contiguous().cuda(), sg.cuda())
+    same = moe.moe_combine(Yp.cuda(), rowp.cuda(), w.cuda(), Sp[0].contiguous().cuda(), sg.cuda())
+    assert torch.equal(one.view(torch.int16), same.view(torch.int16))
+
+
 def test_combine_matches_oracle(moe, oracle64):
     T, H, K = 50, 320, 3
     g = torch.Generator().manual_seed(9)
@@ -610,6 +679,16 @@ def test_prefill_layer_full_size_every_element(moe, oracle64):
     check_close(f64(b2.Yp), Yp, "prefill Yp, benchmark configuration, every element")
     check_close(f64(b2.S), S, "prefill shared expert, benchmark configuration, every element")
     check_close(f64(b2.out), out, "prefill layer output, benchmark configuration, every element")
+    # shared experts hosted by the block call (the benchmark's default): four sets of the routed size
+    b3 = moe.moe_layer_forward(g.x, g.Wr, g.bias, g.Wg, g.Wu, g.Wd, gpu_shared(g), s.K, s.renorm, fused_shared=True)
+    torch.cuda.synchronize()
+    assert b3.S_parts is not None and b3.S_parts.shape[0] == 4
+    parts_ref = oracle_shared_parts(oracle64, d, s.I)
+    check_close(f64(b3.Yp), Yp, "prefill Yp, shared experts in the block call, every element")
+    for i in range(4):
+        check_close(f64(b3.S_parts[i]), parts_ref[i], f"prefill shared expert {i} of 4, every element")
+    check_close(f64(b3.out), out, "prefill layer output, shared experts in the block call, every element")
+    assert torch.equal(b3.Yp.view(torch.int16), b2.Yp.view(torch.int16))
     # the per-token definition on a few tokens (independent of the permutation and of the block form)
     tok = sample_tokens(s.T, 6, 4)
     ref, ids_t, _ = oracle64.token_forward(tok, d["x"], d["Wr"], d["bias"], d["Wg"], d["Wu"], d["Wd"], shared_of(d),
