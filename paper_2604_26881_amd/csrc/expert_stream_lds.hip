@@ -63,6 +63,14 @@ __global__ __launch_bounds__(64) void expert_stream_lds_kernel(GemmArgs a) {
 
   const int N = a.N, Kdim = a.Kdim;
   const int nk = Kdim / 64;
+  // The walk over K starts at step `rot` and wraps around.  Thousands of these waves start within a
+  // few microseconds of each other; if all began at K step 0 their requests of one moment would sit
+  // at the same offset inside the weight rows, which for rows of a power-of-two length (4 KB at
+  // K = 2048) lands them in the same memory channels (measured on the decode batch: gate/up 134 us
+  // with a common start, 121 us with staggered starts; the 2816-byte rows of the down projection
+  // show no difference).  rot depends on the expert and the column block only, so results do not
+  // depend on the block cut.
+  const int rot = (int)(((unsigned)blockIdx.x * 3u + (unsigned)eg * 5u) % (unsigned)nk);
   // this wave's output columns: rows [n0, n0+16) of both branches (gate/up) or rows [n0, n0+32) (down)
   const int n0 = (int)blockIdx.x * NPER;
   if (n0 >= N) return;
@@ -104,7 +112,7 @@ __global__ __launch_bounds__(64) void expert_stream_lds_kernel(GemmArgs a) {
     // K step s into ring slot `slot`: the weights with the read-once hint, the token rows without
     auto issue = [&](int s, int slot) {
       const uint32_t l = lds0 + (uint32_t)slot * S::STAGE;
-      const size_t kb = (size_t)s * 128;
+      const size_t kb = (size_t)(s + rot >= nk ? s + rot - nk : s + rot) * 128;
       copy_to_lds_16_stream(W0 + kb, coffW[0], l);
       copy_to_lds_16_stream(W0 + kb, coffW[1], l + 1024u);
       copy_to_lds_16_stream(W1 + kb, coffW[0], l + 2048u);
