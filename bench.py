@@ -539,7 +539,8 @@ def run_layer_workload(args, moe, cpu_baseline: bool):
             t_cpu += time.perf_counter() - t0
             done += len(tok)
         out["cpu_baseline"] = {"value": done / t_cpu, "unit": "tokens/s", "cores": cores, "kind": "oracle",
-                               "sample": f"first {done} tokens of the same batch, float64 per-token definition, "
+                               "sample": f"first {done} tokens of the same batch, float64 per-token definition "
+                                         f"(the checker as it stands: gcc -O2, no fast-math, OpenMP over tokens), "
                                          f"{t_cpu:.1f} s"}
         if stack:   # one layer was timed; the stack repeats it n_layers times per token
             out["cpu_baseline"]["value"] /= n_layers

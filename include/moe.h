@@ -189,36 +189,11 @@ int moe_combine(const void* Yp, const int32_t* row_of_pair, const float* topk_w,
 int moe_residual_norm(const void* x, const void* y, int T, int H, float eps, void* out, void* stream);
 
 /*
- * The same two calls with the kernel shape picked by the caller instead of by the library
- * (measurement and tuning).  policy: 0 = automatic (what the plain calls use); 3 and 5 = MFMA tiles
- * of 128 token rows by 256 weight rows; 4 = 256 by 256; 8 = 128 by 64 (for the shared expert, whose
- * workspace has room for them, the down projection is cut into up to 8 parts along K whose fp32
- * partial sums a second kernel adds in ascending order; with policy 8 and T > 512 the shared call
- * needs the workspace of moe_shared_workspace_bytes plus 8*T*H*4 bytes); 9 = weight-streaming
- * kernels that stage the weights through wave-private LDS rings (few rows per expert); 10 = MFMA
- * tiles of 128 by 128; 11 = 160 by 256.  Any other number is refused with MOE_ERR_SHAPE.
- * Every policy computes the same function; results may differ in the last bf16 bit between
- * policies because the fp32 summation order differs.  Use one policy for all blocks of a layer.
- * Adding 0x100 to policy runs only the first kernel of the call (gate/up projections and SwiGLU
- * into the workspace), adding 0x200 only the second (down projection from the workspace, and for
- * the shared expert the gate logit): the two halves of one call, so each can be timed alone.
- * Adding 0x400 to the policy of moe_shared_forward_ex (automatic shapes) keeps its first kernel off
- * the one tile shape that occupies every register of a CU, so that small kernels issued on other
- * streams at the same time (gating, micro-batch construction) are not held up behind it.
- */
-int moe_expert_group_forward_ex(int group_lo, int group_hi, const void* Xp,
-                                const int32_t* expert_offsets, const void* Wg, const void* Wu,
-                                const void* Wd, int P, int H, int E, int I, void* Yp,
-                                void* workspace, size_t workspace_bytes, int policy, void* stream);
-int moe_shared_forward_ex(const void* x, const void* Wsg, const void* Wsu, const void* Wsd,
-                          const void* wgate, int T, int H, int Is, void* S, float* sg,
-                          void* workspace, size_t workspace_bytes, int policy, void* stream);
-
-/*
  * The same invocation without a permuted copy of the tokens: row r of the block's batch is read
  * as x[src_of_row[r] / K, :] while the first kernel stages it (the gather of the micro-batch
  * construction, folded into the consumer).  Same result, bit for bit, as
- * moe_expert_group_forward_ex on Xp.  policy as for moe_expert_group_forward_ex (0 = automatic).
+ * moe_expert_group_forward on Xp.  policy: 0 = the library picks the kernel shape; other values are
+ * the tuning knob described in moe_tuning.h.
  *   x [T,H] bf16 with T = P / K; src_of_row [P] int32 on the device, values in [0,P).
  */
 int moe_expert_group_forward_gather(int group_lo, int group_hi, const void* x,
@@ -246,8 +221,8 @@ int moe_expert_group_forward_gather(int group_lo, int group_hi, const void* x,
  * caller uses moe_expert_group_forward(_gather) and moe_shared_forward.  When the routed experts
  * are cut into several blocks, one of the calls carries the shared experts and the others are
  * plain block calls.  x [T,H]; src_of_row [T*K]; weights as in the separate calls.
- * workspace: moe_fused_workspace_bytes(T, K, I, Is) bytes.  policy: 0, 3, 4, 5, 10 or 11 and the
- * 0x100 / 0x200 bits as for moe_expert_group_forward_ex.
+ * workspace: moe_fused_workspace_bytes(T, K, I, Is) bytes.  policy: 0, or one of 3, 4, 5, 10, 11 and the
+ * 0x100 / 0x200 bits of moe_tuning.h.
  */
 #define MOE_SHARED_SETS_MAX 8
 int moe_fused_shared_sets(int T, int H, int E, int K, int I, int Is);
@@ -276,7 +251,7 @@ int moe_combine_parts(const void* Yp, const int32_t* row_of_pair, const float* t
  * expert_ids [n_ids] int32 ON THE DEVICE, distinct values in [0,E) (not checked); the call
  * computes exactly the rows of those experts, with the same result for each row as any other
  * block cut.  tokens is Xp [P,H] when src_of_row is NULL, else x [P/K,H] read through
- * src_of_row as in moe_expert_group_forward_gather.  policy as for moe_expert_group_forward_ex.
+ * src_of_row as in moe_expert_group_forward_gather.  policy: 0, or a value of moe_tuning.h.
  */
 int moe_expert_list_forward(const int32_t* expert_ids, int n_ids, const void* tokens,
                             const int32_t* src_of_row, int K, const int32_t* expert_offsets,

@@ -1,0 +1,46 @@
+/*
+ * moe_tuning.h - the kernel-shape knob of the MoE-layer library, for measurement and tuning.
+ *
+ * Not needed to use the library: the calls of moe.h pick their kernels themselves (policy 0).  This
+ * header documents the `policy` word that some of them accept and declares the two calls of moe.h
+ * that exist in a second form only to take it.  The values may change between builds.
+ */
+#ifndef MOE_TUNING_H_
+#define MOE_TUNING_H_
+
+#include "moe.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/*
+ * moe_expert_group_forward and moe_shared_forward (moe.h) with the kernel shape picked by the caller
+ * instead of by the library.  policy: 0 = automatic (what the plain calls use); 3 and 5 = MFMA tiles
+ * of 128 token rows by 256 weight rows; 4 = 256 by 256; 8 = 128 by 64 (for the shared expert, whose
+ * workspace has room for them, the down projection is cut into up to 8 parts along K whose fp32
+ * partial sums a second kernel adds in ascending order; with policy 8 and T > 512 the shared call
+ * needs the workspace of moe_shared_workspace_bytes plus 8*T*H*4 bytes); 9 = weight-streaming
+ * kernels that stage the weights through wave-private LDS rings (few rows per expert); 10 = MFMA
+ * tiles of 128 by 128; 11 = 160 by 256.  Any other number is refused with MOE_ERR_SHAPE.
+ * Every policy computes the same function; results may differ in the last bf16 bit between
+ * policies because the fp32 summation order differs.  Use one policy for all blocks of a layer.
+ * Adding 0x100 to policy runs only the first kernel of the call (gate/up projections and SwiGLU
+ * into the workspace), adding 0x200 only the second (down projection from the workspace, and for
+ * the shared expert the gate logit): the two halves of one call, so each can be timed alone.
+ * Adding 0x400 to the policy of moe_shared_forward_ex (automatic shapes) keeps its first kernel off
+ * the one tile shape that occupies every register of a CU, so that small kernels issued on other
+ * streams at the same time (gating, micro-batch construction) are not held up behind it.
+ */
+int moe_expert_group_forward_ex(int group_lo, int group_hi, const void* Xp,
+                                const int32_t* expert_offsets, const void* Wg, const void* Wu,
+                                const void* Wd, int P, int H, int E, int I, void* Yp,
+                                void* workspace, size_t workspace_bytes, int policy, void* stream);
+int moe_shared_forward_ex(const void* x, const void* Wsg, const void* Wsu, const void* Wsd,
+                          const void* wgate, int T, int H, int Is, void* S, float* sg,
+                          void* workspace, size_t workspace_bytes, int policy, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOE_TUNING_H_ */

@@ -19,13 +19,13 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-u
 
 
 def source_id() -> str:
-    """SHA-256 over the library's sources (csrc/ and the C header), by file name and content.  The
+    """SHA-256 over the library's sources (csrc/ and the C headers), by file name and content.  The
     build stamps it into the library (moe_build_id); the binding refuses a library whose stamp is not
     the id of the sources beside it, and stored profiler counters carry the id of the kernels they
     were taken on."""
     h = hashlib.sha256()
     files = [os.path.join(CSRC, n) for n in sorted(os.listdir(CSRC))]
-    files.append(os.path.join(os.path.dirname(HERE), "include", "moe.h"))
+    files += [os.path.join(os.path.dirname(HERE), "include", n) for n in ("moe.h", "moe_tuning.h")]
     for path in files:
         with open(path, "rb") as f:
             h.update(os.path.basename(path).encode() + b"\0" + f.read())

@@ -2,6 +2,7 @@
 // Semantics of every call are stated in include/moe.h.
 #include <atomic>
 #include "../../include/moe.h"
+#include "../../include/moe_tuning.h"
 #include "common.h"
 
 using namespace moe;

@@ -18,7 +18,7 @@ def lib():
 
 
 def declared_symbols():
-    text = open(os.path.join(ROOT, "include", "moe.h")).read()
+    text = "".join(open(os.path.join(ROOT, "include", n)).read() for n in ("moe.h", "moe_tuning.h"))
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(moe_[a-z_]+)\s*\(", text)))
 
