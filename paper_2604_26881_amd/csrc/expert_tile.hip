@@ -147,6 +147,15 @@ __global__ __launch_bounds__(256, OCC) void expert_tile_kernel(GemmArgs a) {
   const int nk = Kdim / S::BK / KSPLIT;          // K steps of one work item (a tile, or a K part of it)
   const int groupTiles = S::GM * NT;
   const int Lend = ngrp * groupTiles * KSPLIT;
+  // Divisions of the walk, prepared once per workgroup so that finding a tile costs multiplications only:
+  // light groups among the first g groups of the merged walk = (g * light_ratio) >> 32, with light_ratio =
+  // ceil(grp0 * 2^32 / ngrp): monotone in g, rises by at most one per group, and is exactly grp0 at g = ngrp,
+  // so every group of either class is drawn exactly once; x / groupTiles and pair / gather_div by a
+  // multiply-high with one correction step.
+  const unsigned long long light_ratio = ngrp > 0 ? ((((unsigned long long)grp0) << 32) + (unsigned)ngrp - 1ull) / (unsigned)ngrp : 0ull;
+  const uint32_t gt_magic = groupTiles > 1 ? (uint32_t)(0x100000000ull / (unsigned)groupTiles) : 0u;   // (2^32 itself does not fit)
+  const uint32_t gd = a.gather ? (uint32_t)a.gather_div : 1u;
+  const uint32_t gd_magic = gd > 1u ? (uint32_t)(0x100000000ull / gd) : 0u;
 
   const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
   // copy assignment of this lane inside an 8-row block: row lane/8, 16-byte slot lane%8; the slot
@@ -189,10 +198,15 @@ __global__ __launch_bounds__(256, OCC) void expert_tile_kernel(GemmArgs a) {
       L = xcd_walk ? ((it * 8 + (int)(blockIdx.x & 7)) * run + slot) : (it * G + (int)blockIdx.x);
       if (L >= Lend) { t.valid = false; return t; }
       const int Lt = KSPLIT > 1 ? L / KSPLIT : L;
-      const int grp = Lt / groupTiles, rem = Lt - grp * groupTiles;
+      int grp = Lt, rem = 0;
+      if (groupTiles > 1) {
+        grp = (int)__umulhi((uint32_t)Lt, gt_magic);   // floor(2^32/d) underestimates the quotient by at most one
+        rem = Lt - grp * groupTiles;
+        if (rem >= groupTiles) { ++grp; rem -= groupTiles; }
+      }
       // group grp of the merged walk: light groups are spread evenly between the heavy ones
-      const int before = (int)((long long)grp * grp0 / ngrp);          // light groups among the first grp
-      cls = (int)((long long)(grp + 1) * grp0 / ngrp) > before ? 0 : 1;
+      const int before = (int)(((unsigned long long)(unsigned)grp * light_ratio) >> 32);          // light groups among the first grp
+      cls = (int)(((unsigned long long)(unsigned)(grp + 1) * light_ratio) >> 32) > before ? 0 : 1;
       mrow = (cls == 0 ? before : grp - before) * S::GM + rem % S::GM;
       nt = rem / S::GM;
       if (mrow < (cls == 0 ? total0 : total1)) break;
@@ -240,7 +254,15 @@ __global__ __launch_bounds__(256, OCC) void expert_tile_kernel(GemmArgs a) {
       uint32_t ld = (uint32_t)Kdim;
       if (i < S::NLA) {
         grow = min(row, t.rowsValid - 1);
-        if (gathered) grow = a.gather[t.row0 + grow] / a.gather_div;
+        if (gathered) {
+          const uint32_t pair = (uint32_t)a.gather[t.row0 + grow];
+          uint32_t tok = pair;
+          if (gd > 1u) {
+            tok = __umulhi(pair, gd_magic);
+            if (pair - tok * gd >= gd) ++tok;
+          }
+          grow = (int)tok;
+        }
       } else {
         int r = row - BM;
         if (GATEUP && i >= S::NLA + (S::NL - S::NLA) / 2) r -= BN / 2;   // second half: the up branch
