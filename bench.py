@@ -58,6 +58,38 @@ def measured_traffic(args, kernel: str, build_id: str):
     return None if e is None else e["hbm_bytes_per_launch"]
 
 
+def mfma_sustained(moe, x, W, launches: int = 20, iters: int = 2000):
+    """What the matrix pipes sustain with nothing else running (operands in registers, no memory traffic), on
+    zeros and on operand values taken from the workload (token rows against weight rows): rate from HIP events
+    around `launches` back-to-back launches on every compute unit, shader clock from the kernel's own counters.
+    The chip lowers its clock under dense MFMA work on operands with realistic bit activity, so the second
+    figure, not the published peak, is what a perfect kernel could reach on this data."""
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    half = 16384 // 2     # bf16 values in each half of the operand buffer
+    ops = {"zeros": torch.zeros(2 * half, dtype=torch.bfloat16, device="cuda"),
+           "workload_values": torch.cat([x.reshape(-1)[:half], W.reshape(-1)[:half]]).contiguous()}
+    clocks = torch.zeros(2 * cus, dtype=torch.int64, device="cuda")
+    out = {}
+    for name, o in ops.items():
+        for _ in range(3):
+            moe.moe_probe_mfma(o, iters, cus, clocks)
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(launches):
+            moe.moe_probe_mfma(o, iters, cus, clocks)
+        b.record()
+        torch.cuda.synchronize()
+        sec = a.elapsed_time(b) * 1e-3 / launches
+        c = clocks.cpu().numpy().reshape(cus, 2).astype(float)
+        flops = 2.0 * 32 * 32 * 16 * 16 * iters * 4 * cus
+        out[name] = {"tflops": flops / sec / 1e12, "frac_of_peak": flops / sec / 1e12 / PEAK_MFMA_BF16_TFLOPS,
+                     "shader_clock_mhz": float((c[:, 0] / (c[:, 1] / 100.0)).mean()),
+                     "shader_clocks_per_mfma": float(c[:, 0].mean() / (16.0 * iters))}
+    out["kernel"] = f"{cus} workgroups x 4 waves x {iters} x 16 independent v_mfma_f32_32x32x16_bf16, {launches} launches"
+    return out
+
+
 def run_residency(args, moe) -> int:
     """On-demand expert residency (Sec. 3: blocks are instantiated on demand and released when idle).
     Six tenants (Sec. 4.2) send decode batches of 32 tokens in turn; a strong per-tenant router bias
@@ -168,6 +200,9 @@ def main() -> int:
     ap.add_argument("--with-decode", type=int, default=1,
                     help="prefill workload: 1 (default) also measures the decode batch (T = 128) in the same run and "
                          "attaches it to the JSON line under \"decode\"; 0: prefill only")
+    ap.add_argument("--mfma-probe", type=int, default=1,
+                    help="1: also report what the matrix pipes sustain on zeros and on the workload's values with nothing "
+                         "else running (prefill-sized workloads; adds about 30 ms of GPU time)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     args = ap.parse_args()
@@ -486,6 +521,10 @@ def run_layer_workload(args, moe, cpu_baseline: bool):
         roof = {"bound": "mfma", "achieved": achieved, "peak": PEAK_MFMA_BF16_TFLOPS, "unit": "TFLOP/s",
                 "frac": achieved / PEAK_MFMA_BF16_TFLOPS, "traffic": None}
     roof["traffic"] = measured_traffic(args, dom, moe.build_id())
+    sustained = None
+    if args.mfma_probe and args.workload != "decode":
+        sustained = mfma_sustained(moe, g.x, g.Wg)
+        roof["frac_of_sustained_on_workload_values"] = achieved / sustained["workload_values"]["tflops"]
     roof.update({"kernel": dom, "launch_us": dur_s * 1e6, "launches_per_step": launches,
                  "algorithmic_flops_per_launch": alg_flops[dom] / launches,
                  "algorithmic_bytes_per_launch": alg_bytes[dom] / launches})
@@ -520,6 +559,8 @@ def run_layer_workload(args, moe, cpu_baseline: bool):
         "layer_gbs": layer_bytes / (ms * 1e-3) / 1e9, "layer_frac_of_hbm_peak": layer_bytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
         "flop_per_token": flop_tok, "layer_bytes_algorithmic": layer_bytes, "roofline": roof, "kernels": kernels, "build_id": moe.build_id(),
     }
+    if sustained is not None:
+        out["mfma_sustained"] = sustained
 
     # ---- CPU baseline: the oracle, per-token definition, on a bounded sample of the same batch
     if cpu_baseline:

@@ -40,6 +40,26 @@ int moe_shared_forward_ex(const void* x, const void* Wsg, const void* Wsu, const
                           const void* wgate, int T, int H, int Is, void* S, float* sg,
                           void* workspace, size_t workspace_bytes, int policy, void* stream);
 
+/*
+ * Measurement aid (no part of the paper's method): the rate the matrix pipes sustain on given operand
+ * values with nothing else running, and the shader clock the chip holds meanwhile.  Dense MFMA work
+ * on operands with realistic bit activity makes the chip lower its clock, so the published peak is
+ * out of reach of any kernel on such data; a benchmark can state that ceiling beside its result.
+ * operands: device, MOE_PROBE_OPERAND_BYTES bytes read as bf16 (eight 16-byte MFMA operand fragments
+ * per lane of a 256-lane workgroup; any values: zeros, random numbers, rows of a real tensor).
+ * Each of `workgroups` workgroups (one per compute unit up to the number of compute units) runs four
+ * waves that each issue iters x 16 independent 32x32x16 bf16 MFMAs: 2 * 32*32*16 * 16 * iters * 4 *
+ * workgroups floating-point operations per launch; the caller times the launch.
+ * clocks: device, 2 * workgroups int64, written: per workgroup the ticks of the shader clock and of
+ * the constant 100 MHz clock over its loop (their ratio x 100 MHz = the shader clock held).
+ * Enqueues one kernel on `stream`, allocates nothing, does not synchronize.  Returns MOE_ERR_NULL,
+ * MOE_ERR_SHAPE (operand_bytes too small, iters outside 1 ... 2^20, workgroups outside 1 ... 65535)
+ * or MOE_ERR_LAUNCH.
+ */
+#define MOE_PROBE_OPERAND_BYTES 32768
+int moe_probe_mfma(const void* operands, size_t operand_bytes, int iters, int workgroups,
+                   int64_t* clocks, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -21,7 +21,7 @@ SYMBOLS = ["moe_status_string", "moe_build_id", "moe_route", "moe_route_segments
            "moe_shared_forward", "moe_shared_forward_ex", "moe_combine", "moe_combine_parts",
            "moe_fused_shared_sets", "moe_fused_workspace_bytes", "moe_expert_group_forward_fused",
            "moe_permute_workspace_bytes", "moe_expert_workspace_bytes", "moe_shared_workspace_bytes",
-           "moe_workspace_bytes", "moe_residual_norm"]
+           "moe_workspace_bytes", "moe_residual_norm", "moe_probe_mfma"]
 
 
 class MoeError(RuntimeError):
@@ -97,10 +97,23 @@ def load() -> ctypes.CDLL:
     lib.moe_shared_workspace_bytes.argtypes = [c_int, c_int, c_int]
     lib.moe_residual_norm.restype = c_int
     lib.moe_residual_norm.argtypes = [c_vp, c_vp, c_int, c_int, ctypes.c_float, c_vp, c_vp]
+    lib.moe_probe_mfma.restype = c_int
+    lib.moe_probe_mfma.argtypes = [c_vp, c_sz, c_int, c_int, c_vp, c_vp]
     lib.moe_workspace_bytes.restype = c_sz
     lib.moe_workspace_bytes.argtypes = [c_int] * 6
     _LIB = lib
     return lib
+
+
+def moe_probe_mfma(operands, iters: int, workgroups: int, clocks):
+    """One launch of the MFMA rate probe: operands = at least 32768 bytes of bf16 on the GPU, clocks = int64 GPU
+    tensor of 2 * workgroups entries (shader clock ticks, 100 MHz ticks per workgroup).  The caller times it."""
+    if clocks.numel() < 2 * workgroups:
+        raise MoeError("moe_probe_mfma: clocks needs 2 * workgroups entries")
+    rc = load().moe_probe_mfma(_ptr(operands, torch.bfloat16, "operands"), operands.numel() * operands.element_size(),
+                               int(iters), int(workgroups), _ptr(clocks, torch.int64, "clocks"), _stream())
+    _check(rc, "moe_probe_mfma")
+    return clocks
 
 
 def build_id() -> str:

@@ -11,7 +11,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libmoe_hip.so")
 OBJDIR = os.path.join(HERE, "_build")
-SOURCES = ["api.hip", "route.hip", "permute.hip", "combine.hip", "expert_tile.hip", "expert_stream_lds.hip"]
+SOURCES = ["api.hip", "route.hip", "permute.hip", "combine.hip", "expert_tile.hip", "expert_stream_lds.hip", "mfma_probe.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          # packed-fp32 instructions are switched off for all device code

@@ -121,6 +121,14 @@ extern "C" {
 
 const char* moe_build_id(void) { return MOE_BUILD_ID; }
 
+int moe_probe_mfma(const void* operands, size_t operand_bytes, int iters, int workgroups, int64_t* clocks, void* stream) {
+  if (operands == nullptr || clocks == nullptr) return MOE_ERR_NULL;
+  if (operand_bytes < MOE_PROBE_OPERAND_BYTES || iters < 1 || iters > (1 << 20) || workgroups < 1 || workgroups > 65535)
+    return MOE_ERR_SHAPE;
+  return moe::launch_mfma_probe(operands, iters, workgroups, reinterpret_cast<long long*>(clocks), (hipStream_t)stream) == 0
+             ? MOE_OK : MOE_ERR_LAUNCH;
+}
+
 const char* moe_status_string(int status) {
   switch (status) {
     case MOE_OK: return "ok";

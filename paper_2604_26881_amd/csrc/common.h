@@ -116,6 +116,7 @@ int launch_combine(const void* Yp, const int32_t* row_of_pair, const float* w, c
                    const float* sg, int T, int H, int K, void* out, hipStream_t st);
 int launch_residual_norm(const void* x, const void* y, int T, int H, float eps, void* out, hipStream_t st);
 int launch_gate_dot(const void* x, const void* wgate, int T, int H, float* sg, hipStream_t st);
+int launch_mfma_probe(const void* operands, int iters, int workgroups, long long* clocks, hipStream_t st);
 // Tiled MFMA kernels (many rows per expert) and streaming kernels (few rows per expert).
 int launch_tile_gateup(const GemmArgs& a, int tile_rows, hipStream_t st);
 int launch_tile_down(const GemmArgs& a, int tile_rows, hipStream_t st);

@@ -138,6 +138,13 @@ def test_bad_arguments_are_rejected_before_any_launch(lib):
     assert lib.moe_combine(p, p, p, p, None, 4, 64, 2, p, None) == NULL      # S without sg
     assert lib.moe_combine(p, p, p, None, None, 4, 64, 17, p, None) == SHAPE
     assert lib.moe_combine(None, p, p, None, None, 4, 64, 2, p, None) == NULL
+    # the MFMA rate probe
+    assert lib.moe_probe_mfma(None, 32768, 10, 1, p, None) == NULL
+    assert lib.moe_probe_mfma(p, 32768, 10, 1, None, None) == NULL
+    assert lib.moe_probe_mfma(p, 32767, 10, 1, p, None) == SHAPE            # operand buffer too small
+    assert lib.moe_probe_mfma(p, 32768, 0, 1, p, None) == SHAPE
+    assert lib.moe_probe_mfma(p, 32768, 10, 0, p, None) == SHAPE
+    assert lib.moe_probe_mfma(p, 32768, 10, 65536, p, None) == SHAPE
 
 
 def test_balanced_blocks_partition_and_balance():

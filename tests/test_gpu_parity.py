@@ -1110,3 +1110,23 @@ def test_blocks_on_several_streams_equal_one_stream(moe, oracle64):
     check_close(f64(buf.out), oref["out"], "layer output, blocks on three streams")
     assert torch.equal(buf.Yp.view(torch.int16), ref.Yp.view(torch.int16))
     assert torch.equal(buf.out.view(torch.int16), ref.out.view(torch.int16))
+
+
+@pytest.mark.gpu
+def test_mfma_rate_probe_counts_its_own_clocks(moe):
+    """The measurement aid: every workgroup reports the ticks of both clocks over its loop; one MFMA of this
+    shape occupies a matrix pipe for 32 shader clocks (8 passes of 4), whatever the operands and the clock
+    the chip holds, and the shader clock lies between a few hundred MHz and the 2.4 GHz maximum."""
+    print("[case] MFMA rate probe, 8 workgroups, zeros and N(0,1) operands", flush=True)
+    g = torch.Generator().manual_seed(5)
+    for ops in (torch.zeros(16384, dtype=torch.bfloat16), torch.randn(16384, generator=g).to(torch.bfloat16)):
+        clocks = torch.zeros(16, dtype=torch.int64, device="cuda")
+        moe.moe_probe_mfma(ops.cuda(), 500, 8, clocks)
+        torch.cuda.synchronize()
+        c = clocks.cpu().numpy().reshape(8, 2).astype(float)
+        per_mfma = c[:, 0] / (16 * 500)
+        mhz = c[:, 0] / (c[:, 1] / 100.0)
+        assert np.all(per_mfma > 31.9) and np.all(per_mfma < 36.0), per_mfma
+        assert np.all(mhz > 300.0) and np.all(mhz < 2500.0), mhz
+    with pytest.raises(moe.MoeError):
+        moe.moe_probe_mfma(torch.zeros(100, dtype=torch.bfloat16, device="cuda"), 10, 1, torch.zeros(2, dtype=torch.int64, device="cuda"))
