@@ -553,7 +553,11 @@ def run_layer_workload(args, moe, cpu_baseline: bool):
                    "shared_expert": ("inside the first block call, as Is / I experts on every token" if fshared else
                                      "second stream, concurrent with the routed path" if overlap else "same stream"),
                    "active_experts": active, "rows_per_expert_max": int(counts.max()),
-                   "rows_per_expert_median": float(np.median(counts))},
+                   "rows_per_expert_median": float(np.median(counts)),
+                   "rows_per_expert_histogram": {
+                       "bin_upper_edges": [0, 32, 64, 128, 160, 256, 320, 512, 1024, "inf"],
+                       "experts": [int(v) for v in np.histogram(
+                           counts, bins=[-0.5, 0.5, 32.5, 64.5, 128.5, 160.5, 256.5, 320.5, 512.5, 1024.5, 1e9])[0]]}},
         "ms_per_step_eager": eager_ms, "ms_per_step_graph": graph_ms,
         "layer_tflops": layer_tflops, "layer_frac_of_mfma_peak": layer_tflops / PEAK_MFMA_BF16_TFLOPS,
         "layer_gbs": layer_bytes / (ms * 1e-3) / 1e9, "layer_frac_of_hbm_peak": layer_bytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
