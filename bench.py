@@ -203,6 +203,9 @@ def main() -> int:
     ap.add_argument("--mfma-probe", type=int, default=1,
                     help="1: also report what the matrix pipes sustain on zeros and on the workload's values with nothing "
                          "else running (prefill-sized workloads; adds about 30 ms of GPU time)")
+    ap.add_argument("--tile-clocks", type=int, default=1,
+                    help="1: the MFMA tile kernels of the eager region record their workgroups' clocks (shader clock held, "
+                         "share of the K loops); reported per kernel under kernels.*.tile_clocks")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     args = ap.parse_args()
@@ -321,6 +324,10 @@ def run_layer_workload(args, moe, cpu_baseline: bool):
         for st in block_streams:
             main.wait_stream(st)
 
+    # clock records of the four grouped-GEMM launches (one buffer each, room for 1024 workgroups)
+    clock_bufs = ([torch.zeros(4 * 1024, dtype=torch.int64, device="cuda") for _ in range(4)]
+                  if args.tile_clocks and len(groups) == 1 and not fshared else [])
+
     def layer_step(x, w, events=None):
         sh = (w["Wsg"], w["Wsu"], w["Wsd"], w["wgate"]) if s.Is > 0 else None
         if overlap and events is None:
@@ -359,22 +366,31 @@ def run_layer_workload(args, moe, cpu_baseline: bool):
                 torch.cuda.current_stream().wait_stream(side_stream)
         else:
             # same kernels, launched one per call so that events can bracket each of them
+            # (each launch also records its workgroups' clocks into a buffer of its own when the MFMA tile kernels
+            # serve it; the last step's records are read after the region)
             ev = [[torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)] for _ in names]
+            clk = (lambda i: moe.moe_tile_clock_buffer(clock_bufs[i])) if clock_bufs else (lambda i: None)
+            clk(0)
             ev[0][0].record()
             run_blocks(x, w, args.policy | GU)
             ev[0][1].record()
+            clk(1)
             ev[1][0].record()
             run_blocks(x, w, args.policy | DN)
             ev[1][1].record()
             if sh is not None:
+                clk(2)
                 ev[2][0].record()
                 # (with the same "leave room" bit as in the timed step, so the figure is for the shape the step runs)
                 moe.moe_shared_forward(x, *sh, buf.S, buf.sg, buf.workspace_shared,
                                        args.shared_policy | GU | (0x400 if overlap else 0))
                 ev[2][1].record()
+                clk(3)
                 ev[3][0].record()
                 moe.moe_shared_forward(x, *sh, buf.S, buf.sg, buf.workspace_shared, args.shared_policy | DN)
                 ev[3][1].record()
+            if clock_bufs:
+                moe.moe_tile_clock_buffer(None)
             events.append(ev)
         moe.moe_combine(buf.Yp, buf.row_of_pair, buf.topk_w, buf.S, buf.sg, buf.out)
 
@@ -530,6 +546,17 @@ def run_layer_workload(args, moe, cpu_baseline: bool):
                  "algorithmic_bytes_per_launch": alg_bytes[dom] / launches})
     kernels = {n: {"ms_per_step": kern_ms[n], "tflops": alg_flops[n] / (kern_ms[n] * 1e-3) / 1e12,
                    "gbs": alg_bytes[n] / (kern_ms[n] * 1e-3) / 1e9} for n in kern_ms}
+    # the shader clock the chip held inside the tile kernels of the last eager step (workgroups that recorded)
+    for i, n in enumerate(names):
+        if clock_bufs and n in kernels:
+            c = clock_bufs[i].cpu().numpy().reshape(-1, 4).astype(float)
+            c = c[c[:, 3] > 0]
+            if len(c):
+                kernels[n]["tile_clocks"] = {
+                    "workgroups": int(len(c)), "tiles": int(c[:, 3].sum()),
+                    "shader_clock_mhz": float((c[:, 0] / (c[:, 1] / 100.0)).mean()),
+                    "k_loop_share_of_workgroup_clocks": float(c[:, 2].sum() / c[:, 0].sum()),
+                    "k_loop_shader_clocks_per_tile": float(c[:, 2].sum() / c[:, 3].sum())}
 
     # whole-layer fractions against both roofs (weights of active experts + shared + activations)
     layer_bytes = (sum(alg_bytes[n] for n in kern_ms) + s.E * s.H * 2 + 2 * s.T * s.H * 2 + 2 * P * s.H * 2) * n_layers

@@ -60,6 +60,23 @@ int moe_shared_forward_ex(const void* x, const void* Wsg, const void* Wsu, const
 int moe_probe_mfma(const void* operands, size_t operand_bytes, int iters, int workgroups,
                    int64_t* clocks, void* stream);
 
+/*
+ * Measurement aid: the shader clock the chip holds while the MFMA tile kernels of this library run.
+ * After moe_tile_clock_buffer(clocks, n) every tile-kernel launch made by the calling host thread
+ * (the grouped GEMMs of moe_expert_group_forward*, moe_expert_list_forward and moe_shared_forward
+ * at prefill-sized batches; the weight-streaming kernels do not record) writes, for each of its
+ * workgroups b < n, four int64 at clocks[4*b]: ticks of the shader clock and ticks of the constant
+ * 100 MHz clock between the workgroup's start and end (ratio x 100 MHz = the clock held), the
+ * shader-clock ticks it spent inside the K loops of its tiles, and the number of its tiles.
+ * Workgroups that find no tile write nothing; a later launch overwrites an earlier one's record.
+ * clocks: device memory of 4*n int64, owned by the caller, which keeps it alive until the launches
+ * have finished or the buffer is switched off with moe_tile_clock_buffer(NULL, 0).  The setting is
+ * per host thread; the kernels read the clocks in either case (two scalar reads per tile) and only
+ * skip the store when it is off.
+ * Returns MOE_ERR_SHAPE for a buffer with n < 1.
+ */
+int moe_tile_clock_buffer(int64_t* clocks, int workgroups);
+
 #ifdef __cplusplus
 }
 #endif

@@ -21,7 +21,7 @@ SYMBOLS = ["moe_status_string", "moe_build_id", "moe_route", "moe_route_segments
            "moe_shared_forward", "moe_shared_forward_ex", "moe_combine", "moe_combine_parts",
            "moe_fused_shared_sets", "moe_fused_workspace_bytes", "moe_expert_group_forward_fused",
            "moe_permute_workspace_bytes", "moe_expert_workspace_bytes", "moe_shared_workspace_bytes",
-           "moe_workspace_bytes", "moe_residual_norm", "moe_probe_mfma"]
+           "moe_workspace_bytes", "moe_residual_norm", "moe_probe_mfma", "moe_tile_clock_buffer"]
 
 
 class MoeError(RuntimeError):
@@ -97,12 +97,23 @@ def load() -> ctypes.CDLL:
     lib.moe_shared_workspace_bytes.argtypes = [c_int, c_int, c_int]
     lib.moe_residual_norm.restype = c_int
     lib.moe_residual_norm.argtypes = [c_vp, c_vp, c_int, c_int, ctypes.c_float, c_vp, c_vp]
+    lib.moe_tile_clock_buffer.restype = c_int
+    lib.moe_tile_clock_buffer.argtypes = [c_vp, c_int]
     lib.moe_probe_mfma.restype = c_int
     lib.moe_probe_mfma.argtypes = [c_vp, c_sz, c_int, c_int, c_vp, c_vp]
     lib.moe_workspace_bytes.restype = c_sz
     lib.moe_workspace_bytes.argtypes = [c_int] * 6
     _LIB = lib
     return lib
+
+
+def moe_tile_clock_buffer(clocks):
+    """Switch the clock record of the tile kernels on (clocks = int64 GPU tensor of 4 * n entries, n workgroups
+    recorded) or off (None) for launches made by this host thread."""
+    if clocks is None:
+        _check(load().moe_tile_clock_buffer(None, 0), "moe_tile_clock_buffer")
+        return
+    _check(load().moe_tile_clock_buffer(_ptr(clocks, torch.int64, "clocks"), clocks.numel() // 4), "moe_tile_clock_buffer")
 
 
 def moe_probe_mfma(operands, iters: int, workgroups: int, clocks):

@@ -7,6 +7,11 @@ import subprocess
 import sys
 from concurrent.futures import ThreadPoolExecutor
 
+try:
+    from . import mfma_hazards
+except ImportError:      # run as a script
+    import mfma_hazards
+
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libmoe_hip.so")
@@ -36,8 +41,11 @@ def source_id() -> str:
 
 
 def _compile(src: str) -> str:
-    obj = os.path.join(OBJDIR, os.path.splitext(src)[0] + ".o")
-    cmd = [HIPCC, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+    stem = os.path.splitext(src)[0]
+    obj = os.path.join(OBJDIR, stem + ".o")
+    # -save-temps=obj leaves the device assembly beside the object: the MFMA kernels' own code is checked
+    # for result registers touched before the matrix pipe has written them (mfma_hazards.py)
+    cmd = [HIPCC, *FLAGS, "-save-temps=obj", "-c", os.path.join(CSRC, src), "-o", obj]
     if src == "api.hip":
         cmd.append(f'-DMOE_BUILD_ID="{source_id()}"')
     r = subprocess.run(cmd, capture_output=True, text=True)
@@ -46,6 +54,15 @@ def _compile(src: str) -> str:
         raise RuntimeError(f"hipcc failed on {src}:\n{err}")
     if err.strip():
         sys.stderr.write(err + "\n")
+    asm = os.path.join(OBJDIR, f"{stem}-hip-amdgcn-amd-amdhsa-gfx950.s")
+    if not os.path.exists(asm):
+        raise RuntimeError(f"hipcc left no device assembly for {src} (expected {asm})")
+    bad = mfma_hazards.check_file(asm)
+    for n in os.listdir(OBJDIR):     # the other intermediate files are of no further use (several MB per source)
+        if n.startswith(stem + "-") or n.startswith(stem + ".hip-"):
+            os.remove(os.path.join(OBJDIR, n))
+    if bad:
+        raise RuntimeError(f"{src}: the emitted code touches MFMA results before they are written back:\n  " + "\n  ".join(bad))
     return obj
 
 

@@ -121,6 +121,12 @@ extern "C" {
 
 const char* moe_build_id(void) { return MOE_BUILD_ID; }
 
+int moe_tile_clock_buffer(int64_t* clocks, int workgroups) {
+  if (clocks != nullptr && workgroups < 1) return MOE_ERR_SHAPE;
+  moe::set_tile_clock_buffer(reinterpret_cast<long long*>(clocks), clocks == nullptr ? 0 : workgroups);
+  return MOE_OK;
+}
+
 int moe_probe_mfma(const void* operands, size_t operand_bytes, int iters, int workgroups, int64_t* clocks, void* stream) {
   if (operands == nullptr || clocks == nullptr) return MOE_ERR_NULL;
   if (operand_bytes < MOE_PROBE_OPERAND_BYTES || iters < 1 || iters > (1 << 20) || workgroups < 1 || workgroups > 65535)

@@ -105,7 +105,14 @@ struct GemmArgs {
   int ldb_shared;
   const bf16_t* As;        // not nullptr: set s reads its token rows from As[0 .. shared_rows) instead of A (gate/up: x)
   bf16_t* Cs;              // not nullptr: row r of set s goes to Cs[s*shared_rows + r] instead of C (down: the S parts)
+  // Measurement aid (tile kernels; nullptr: off): workgroup b < clock_groups writes four values at clocks[4*b]:
+  // shader-clock ticks and ticks of the constant 100 MHz clock between its start and its end, the shader-clock
+  // ticks it spent inside the K loops of its tiles, and the number of its tiles.
+  long long* clocks;
+  int clock_groups;
 };
+// Where the tile-kernel launches of the calling host thread record their clocks (nullptr: nowhere).
+void set_tile_clock_buffer(long long* clocks, int groups);
 
 // bias [E] for all tokens (seg == nullptr), or bias [n_seg, E] with seg [n_seg + 1] segment bounds on the device
 int launch_route(const void* x, const void* Wr, const float* bias, const int32_t* seg, int n_seg, int T, int H, int E,

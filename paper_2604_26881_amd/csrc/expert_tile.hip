@@ -277,6 +277,14 @@ __global__ __launch_bounds__(256, OCC) void expert_tile_kernel(GemmArgs a) {
     return t;
   };
 
+  // Clock record of this workgroup (a measurement aid).  The clocks are read whether or not a record was asked
+  // for (two scalar reads per tile): a branch between a K loop's last MFMAs and the epilogue's first read of the
+  // accumulators would sit exactly where the compiler has to pad that pair with wait states, and it does not
+  // look across such a branch (build.py checks the emitted code for this).  Only the final store is conditional.
+  const bool clocked = a.clocks != nullptr && (int)blockIdx.x < a.clock_groups;
+  long long clk_kloops = 0, clk_tiles = 0;
+  const long long clk_begin = clock64(), wall_begin = wall_clock64();
+
   TileState cur = next_tile();
   while (cur.valid) {
     const int row0 = cur.row0, rowEnd = cur.rowEnd, rowsValid = cur.rowsValid, n0 = cur.n0, ks = cur.ks;
@@ -402,6 +410,7 @@ __global__ __launch_bounds__(256, OCC) void expert_tile_kernel(GemmArgs a) {
     // token blocks of this wave that hold rows of the expert (at least one, so that the copies and
     // operand reads keep their places between MFMAs)
     const int tbv = min(S::TB, max(1, (rowsValid - wm * S::WTM + 31) >> 5));
+    const long long clk_k0 = clock64();
     switch (tbv) {
       case 1: pipeline(std::integral_constant<int, 1>{}); break;
       case 2: if constexpr (S::TB >= 2) pipeline(std::integral_constant<int, 2>{}); break;
@@ -410,6 +419,8 @@ __global__ __launch_bounds__(256, OCC) void expert_tile_kernel(GemmArgs a) {
       default: if constexpr (S::TB >= 5) pipeline(std::integral_constant<int, 5>{}); break;
     }
     static_assert(S::TB <= 5, "token blocks per wave");
+    clk_kloops += clock64() - clk_k0;
+    ++clk_tiles;
 #undef MOE_TILE_READ1
 #undef MOE_TILE_MFMA1
 #undef MOE_TILE_SLICE
@@ -487,6 +498,20 @@ __global__ __launch_bounds__(256, OCC) void expert_tile_kernel(GemmArgs a) {
   }
 #undef MOE_TILE_ISSUE1
 #undef MOE_TILE_ISSUE
+  if (clocked && tid == 0) {
+    long long* rec = a.clocks + 4 * (size_t)blockIdx.x;
+    rec[0] = clock64() - clk_begin;
+    rec[1] = wall_clock64() - wall_begin;
+    rec[2] = clk_kloops;
+    rec[3] = clk_tiles;
+  }
+}
+
+static thread_local long long* t_clock_buffer = nullptr;
+static thread_local int t_clock_groups = 0;
+void set_tile_clock_buffer(long long* clocks, int groups) {
+  t_clock_buffer = groups > 0 ? clocks : nullptr;
+  t_clock_groups = clocks != nullptr && groups > 0 ? groups : 0;
 }
 
 // Compute units of the current device (asked on every launch: nothing is cached across devices or threads).
@@ -542,7 +567,10 @@ static int launch_tile_t(const GemmArgs& a, hipStream_t st) {
   const long resident = (long)num_cus() * OCC;
   int grid = (int)(bound < resident ? bound : resident);
   if (grid <= 0) return 0;
-  hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, st, a);
+  GemmArgs launched = a;
+  launched.clocks = t_clock_buffer;
+  launched.clock_groups = t_clock_groups;
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, st, launched);
   if (hipGetLastError() != hipSuccess) return -4;
   if (KSPLIT > 1) {
     const long n4 = (long)a.rows_total * a.N / 4;

@@ -138,6 +138,11 @@ def test_bad_arguments_are_rejected_before_any_launch(lib):
     assert lib.moe_combine(p, p, p, p, None, 4, 64, 2, p, None) == NULL      # S without sg
     assert lib.moe_combine(p, p, p, None, None, 4, 64, 17, p, None) == SHAPE
     assert lib.moe_combine(None, p, p, None, None, 4, 64, 2, p, None) == NULL
+    # the clock record of the tile kernels (a per-thread setting, no GPU call)
+    assert lib.moe_tile_clock_buffer(p, 0) == SHAPE
+    assert lib.moe_tile_clock_buffer(p, -3) == SHAPE
+    assert lib.moe_tile_clock_buffer(None, 0) == 0
+    assert lib.moe_tile_clock_buffer(None, 7) == 0                          # off, whatever the count
     # the MFMA rate probe
     assert lib.moe_probe_mfma(None, 32768, 10, 1, p, None) == NULL
     assert lib.moe_probe_mfma(p, 32768, 10, 1, None, None) == NULL

@@ -1130,3 +1130,45 @@ def test_mfma_rate_probe_counts_its_own_clocks(moe):
         assert np.all(mhz > 300.0) and np.all(mhz < 2500.0), mhz
     with pytest.raises(moe.MoeError):
         moe.moe_probe_mfma(torch.zeros(100, dtype=torch.bfloat16, device="cuda"), 10, 1, torch.zeros(2, dtype=torch.int64, device="cuda"))
+
+
+@pytest.mark.gpu
+def test_tile_kernels_record_their_clocks_without_changing_the_result(moe, many_tiles_case):
+    """The measurement aid of the tile kernels: with a clock buffer set, every workgroup that had tiles reports
+    them; their number over the launch is the number of tiles the block has at that tile shape (every tile
+    walked exactly once), the K loops lie inside the workgroup's lifetime, the clock is a plausible shader
+    clock, and the output is bit-identical to the launch without the record."""
+    c, m = MANY_TILES, many_tiles_case
+    T, K, E, H, I = c["T"], c["K"], c["E"], c["H"], c["I"]
+    P = T * K
+    counts = np.diff(m["off"])
+    dev = {k: m[k].cuda() for k in ("Wg", "Wu", "Wd", "Xp")}
+    off = torch.from_numpy(m["off"]).cuda()
+    ws = torch.empty(int(moe.load().moe_expert_workspace_bytes(P, I)), dtype=torch.uint8, device="cuda")
+    token_tiles = int(np.sum((counts + 159) // 160))
+    expect = {0x100: token_tiles * ((I + 127) // 128), 0x200: token_tiles * ((H + 255) // 256)}   # policy 11: 160-row tiles
+    print(f"[case] clock record of the tile kernels, policy 11: {token_tiles} token tiles, expecting {expect}", flush=True)
+    outs = []
+    for record in (False, True):
+        Yp = torch.full((P, H), 768.0, dtype=torch.bfloat16, device="cuda")
+        for phase in (0x100, 0x200):
+            clocks = torch.zeros(4 * 1024, dtype=torch.int64, device="cuda")
+            if record:
+                moe.moe_tile_clock_buffer(clocks)
+            try:
+                moe.moe_expert_group_forward(0, E, dev["Xp"], off, dev["Wg"], dev["Wu"], dev["Wd"], Yp, ws, 11 | phase)
+                torch.cuda.synchronize()
+            finally:
+                moe.moe_tile_clock_buffer(None)
+            rec = clocks.cpu().numpy().reshape(-1, 4)
+            if not record:
+                assert not rec.any()
+                continue
+            rec = rec[rec[:, 3] > 0].astype(float)
+            assert int(rec[:, 3].sum()) == expect[phase], (int(rec[:, 3].sum()), expect[phase])
+            assert np.all(rec[:, 2] > 0) and np.all(rec[:, 2] < rec[:, 0])
+            mhz = rec[:, 0] / (rec[:, 1] / 100.0)
+            assert np.all(mhz > 300.0) and np.all(mhz < 2500.0), (mhz.min(), mhz.max())
+        outs.append(Yp.clone())
+    assert torch.equal(outs[0], outs[1])
+    check_close(f64(outs[1]), m["ref"], "Yp with the clock record on")
