@@ -2,8 +2,10 @@
  * moe_tuning.h - the kernel-shape knob of the MoE-layer library, for measurement and tuning.
  *
  * Not needed to use the library: the calls of moe.h pick their kernels themselves (policy 0).  This
- * header documents the `policy` word that some of them accept and declares the two calls of moe.h
- * that exist in a second form only to take it.  The values may change between builds.
+ * header documents the `policy` word that some of them accept, declares the two calls of moe.h
+ * that exist in a second form only to take it (the values may change between builds), and two
+ * measurement aids: the rate the matrix pipes sustain on given operand values (moe_probe_mfma) and
+ * the clocks the MFMA tile kernels record about themselves on request (moe_tile_clock_buffer).
  */
 #ifndef MOE_TUNING_H_
 #define MOE_TUNING_H_
