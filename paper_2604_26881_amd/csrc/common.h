@@ -56,15 +56,17 @@ __device__ __forceinline__ void trade_halves(uint32_t& a, uint32_t& b) {
 // One 16-byte-per-lane copy from global memory straight into LDS (no registers in between):
 // lane l of the wave writes LDS bytes [lds + 16*l, +16) from global address base + voff.
 // The copy is asynchronous; it is counted by vmcnt like any other vector memory load.
+// (One wait state between the write of m0 and the instruction that reads it: the ISA asks for it, and the
+// compiler, which pads its own such pairs, does not look inside an asm statement.)
 __device__ __forceinline__ void copy_to_lds_16(const void* base, uint32_t voff, uint32_t lds) {
-  asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(base), "s"(lds)
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(base), "s"(lds)
                : "memory", "m0");
 }
 // The same copy with the non-temporal hint: for data that is read once (streamed weights), so that
 // it does not displace reusable lines from the caches.  Measured on a 1 GiB stream of 4 KB rows:
 // 6.0 TB/s without the hint, 6.8 TB/s with it.
 __device__ __forceinline__ void copy_to_lds_16_stream(const void* base, uint32_t voff, uint32_t lds) {
-  asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1 nt" ::"v"(voff), "s"(base), "s"(lds)
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1 nt" ::"v"(voff), "s"(base), "s"(lds)
                : "memory", "m0");
 }
 template <int N>

@@ -1,4 +1,4 @@
-"""Build-time check of the kernels' own assembly for one hazard the hardware does not interlock.
+"""Build-time check of the kernels' own assembly for two hazards the hardware does not interlock.
 
 On CDNA an MFMA's result registers may not be read or overwritten by a non-MFMA instruction until
 the matrix pipe has written them back: the ISA asks for a number of wait states (independent
@@ -9,6 +9,10 @@ the epilogue's first reads of the accumulators, is not padded, and the epilogue 
 accumulators (seen once in this library: one accumulator element per 32-column block wrong by
 the last K slice's contribution).  This module follows every control-flow path backwards from each
 instruction that touches an MFMA's result and fails the build if fewer wait states lie between.
+
+A second, simpler check covers the other pair this library's code can get wrong: a load that writes LDS
+(global_load_lds_*) takes its LDS address from m0 and needs one wait state after a scalar write of m0.
+The compiler pads the pairs it emits itself, but the copies here are asm statements it does not look into.
 
 It reads the device assembly hipcc writes for this library's own sources (-save-temps), nothing else.
 """
@@ -109,6 +113,20 @@ def hazards_in_kernel(body: List[str]) -> List[Tuple[str, str, int, int]]:
     return found
 
 
+def m0_hazards_in_kernel(body: List[str]) -> List[Tuple[str, str]]:
+    """(m0 write, LDS-DMA load) pairs with no instruction between them.  A global/buffer load that writes LDS
+    takes its LDS address from m0 and needs one wait state after a scalar write of m0; the pairs here come
+    from this library's own asm statements, which the compiler does not pad."""
+    ins = [t for t in body if not (t.startswith(".") or t.endswith(":"))]
+    found = []
+    for prev, cur in zip(ins, ins[1:]):
+        op = cur.split()[0]
+        if "_lds_" in op and op.startswith(("global_load", "buffer_load")) and prev.startswith("s_") \
+                and re.match(r"^s_\w+\s+m0\b", prev):
+            found.append((prev, cur))
+    return found
+
+
 def check_file(path: str) -> List[str]:
     """One line per kernel of the assembly file that has a violation."""
     out = []
@@ -118,4 +136,7 @@ def check_file(path: str) -> List[str]:
             u, t, d, need = min(bad, key=lambda b: b[2])
             out.append(f"{name}: {len(bad)} place(s) where an MFMA result is touched too early; the closest: "
                        f"`{t}` {d} wait states after `{u}` (needs {need})")
+        m0 = m0_hazards_in_kernel(body)
+        if m0:
+            out.append(f"{name}: {len(m0)} LDS-writing load(s) directly behind the write of m0, e.g. `{m0[0][0]}` / `{m0[0][1]}`")
     return out

@@ -62,3 +62,12 @@ def test_results_in_ordinary_registers_and_the_shorter_mfma(tmp_path):
             "\tv_mfma_f32_16x16x32_bf16 v[10:13], v[2:5], v[6:9], v[10:13]\n"
             "\ts_cbranch_scc1 .LBB0_1\n")
     assert len(flagged(tmp_path, loop)) == 1
+
+
+def test_lds_writing_load_directly_behind_the_write_of_m0(tmp_path):
+    bad = "\ts_mov_b32 m0, s5\n\tglobal_load_lds_dwordx4 v2, s[4:5]\n"
+    out = flagged(tmp_path, bad)
+    assert len(out) == 1 and "m0" in out[0]
+    assert flagged(tmp_path, "\ts_mov_b32 m0, s5\n\ts_nop 0\n\tglobal_load_lds_dwordx4 v2, s[4:5]\n") == []
+    assert flagged(tmp_path, "\ts_add_i32 m0, s0, 0x400\n\tglobal_load_lds_dwordx4 v[2:3], off\n") != []
+    assert flagged(tmp_path, "\ts_mov_b32 m0, s5\n\tv_mov_b32_e32 v1, v2\n\tglobal_load_lds_dwordx4 v2, s[4:5] nt\n") == []
