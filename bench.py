@@ -48,7 +48,7 @@ def measured_traffic(args, kernel: str, build_id: str):
     such record for this workload and launch configuration, or the record was taken on another build
     of the library than the one loaded (its id is the hash of the sources it was built from)."""
     path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "hbm_traffic.json")
-    if args.policy != 0 or args.shared_policy != 0 or args.group_size != 0 or not os.path.exists(path):
+    if args.policy != 0 or args.shared_policy != 0 or args.group_size != 0 or args.tokens != 0 or not os.path.exists(path):
         return None
     with open(path) as f:
         rec = json.load(f)
@@ -166,6 +166,9 @@ def main() -> int:
                     help="residency workload: factor on the tenants' router biases (how strongly a tenant keeps to "
                          "its own expert subset)")
     ap.add_argument("--layers", type=int, default=24, help="layers of the stack workload")
+    ap.add_argument("--tokens", type=int, default=0,
+                    help="batch size T of the prefill (Zipf-skewed routing) or decode (unbiased routing) workload instead of "
+                         "its own 4096 / 128: for sweeps over the batch size (0: the workload's own)")
     ap.add_argument("--group-size", type=int, default=0, help="experts per expert block (0: one block)")
     ap.add_argument("--route-per-tenant", action="store_true",
                     help="tenants/stack workloads: one gating launch per tenant slice instead of one for the batch")
@@ -253,7 +256,11 @@ def run_layer_workload(args, moe, cpu_baseline: bool):
         layer_w = [wl.tensors()] + [workloads.stack_layer_weights(l, device="cuda") for l in range(1, args.layers)]
         g = wl.to("cuda")
     else:
-        wl = {"prefill": workloads.prefill, "decode": workloads.decode, "tenants": workloads.tenants}[args.workload]()
+        make = {"prefill": workloads.prefill, "decode": workloads.decode, "tenants": workloads.tenants}[args.workload]
+        if args.tokens > 0 and args.workload == "tenants":
+            print("bench.py: --tokens applies to the prefill and decode workloads", file=sys.stderr)
+            return None
+        wl = make(T=args.tokens) if args.tokens > 0 else make()
         s = wl.shape
         g = wl.to("cuda")
         layer_w = [g.tensors()]
@@ -528,7 +535,9 @@ def run_layer_workload(args, moe, cpu_baseline: bool):
     # Which roof: the grouped GEMMs of prefill-sized batches are matrix-core work (the target is a
     # fraction of the bf16 MFMA peak); at decode sizes the same kernels stream weights (HBM).
     # Both figures of every kernel are in "kernels".
-    if args.workload == "decode":
+    # (the library's own switch to the weight-streaming kernels, or the caller's choice of them)
+    streaming = (args.policy & 0xff) == 9 or ((args.policy & 0xff) == 0 and s.E >= 16 and P // s.E <= 26)
+    if streaming:
         achieved = alg_bytes[dom] / launches / dur_s / 1e9
         roof = {"bound": "hbm", "achieved": achieved, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                 "frac": achieved / PEAK_HBM_GBS, "traffic": None}
@@ -538,7 +547,7 @@ def run_layer_workload(args, moe, cpu_baseline: bool):
                 "frac": achieved / PEAK_MFMA_BF16_TFLOPS, "traffic": None}
     roof["traffic"] = measured_traffic(args, dom, moe.build_id())
     sustained = None
-    if args.mfma_probe and args.workload != "decode":
+    if args.mfma_probe and not streaming:
         sustained = mfma_sustained(moe, g.x, g.Wg)
         roof["frac_of_sustained_on_workload_values"] = achieved / sustained["workload_values"]["tflops"]
     roof.update({"kernel": dom, "launch_us": dur_s * 1e6, "launches_per_step": launches,

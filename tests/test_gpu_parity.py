@@ -638,6 +638,24 @@ def test_decode_layer_full_size_every_element(moe, oracle64):
     check_close(f64(buf.out), out, "decode layer output")
 
 
+@pytest.mark.gpu
+@pytest.mark.parametrize("T", [128, 384])
+def test_decode_sized_batch_with_a_hot_expert_every_element(moe, oracle64, T):
+    # the decode-sized batch with the Zipf-skewed router bias: the weight-streaming kernels serve it (26 rows per
+    # expert or fewer on average) while one expert holds nearly every token, i.e. many passes over its weights,
+    # dealt to several workgroups; most experts have a handful of rows or none
+    wl = workloads.prefill(T=T)
+    s = wl.shape
+    buf, r, d = compare_layer(moe, oracle64, wl)
+    counts = np.diff(r["offsets"])
+    print(f"[case] hot expert at T={T}: rows/expert max {counts.max()} median {int(np.median(counts))} "
+          f"empty {int((counts == 0).sum())}", flush=True)
+    assert s.P // s.E <= 26 and counts.max() > 0.9 * T
+    Yp, S, sg, out = oracle_path(oracle64, r, d, s)
+    check_close(f64(buf.Yp), Yp, f"Yp, hot expert, T={T}")
+    check_close(f64(buf.out), out, f"layer output, hot expert, T={T}")
+
+
 def sample_tokens(T, n, seed):
     rng = np.random.default_rng(seed)
     tok = np.unique(np.concatenate([[0, T - 1], rng.integers(0, T, size=n)])).astype(np.int32)
