@@ -565,7 +565,11 @@ def run_layer_workload(args, moe, cpu_baseline: bool):
                     "workgroups": int(len(c)), "tiles": int(c[:, 3].sum()),
                     "shader_clock_mhz": float((c[:, 0] / (c[:, 1] / 100.0)).mean()),
                     "k_loop_share_of_workgroup_clocks": float(c[:, 2].sum() / c[:, 0].sum()),
-                    "k_loop_shader_clocks_per_tile": float(c[:, 2].sum() / c[:, 3].sum())}
+                    "k_loop_shader_clocks_per_tile": float(c[:, 2].sum() / c[:, 3].sum()),
+                    # a persistent workgroup's lifetime (100 MHz ticks): they start together, so the spread is the
+                    # launch's tail (compute units idle while the last workgroups finish)
+                    "workgroup_lifetime_us": {"min": float(c[:, 1].min() / 100.0), "mean": float(c[:, 1].mean() / 100.0),
+                                              "max": float(c[:, 1].max() / 100.0)}}
 
     # whole-layer fractions against both roofs (weights of active experts + shared + activations)
     layer_bytes = (sum(alg_bytes[n] for n in kern_ms) + s.E * s.H * 2 + 2 * s.T * s.H * 2 + 2 * P * s.H * 2) * n_layers
